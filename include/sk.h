@@ -1,0 +1,130 @@
+/*
+ * libsk -- forward and backward pass of the sketched linear layer (SKLinear)
+ * on AMD MI355X (gfx950).  Plain C ABI: device pointers, sizes, a stream.
+ *
+ * The layer (paper Sec. 3.1, "During Development use-case"): the output is the
+ * average over num_terms (= l) sketched matrix products, each of rank low_rank
+ * (= k), and the layer is a drop-in for a dense linear layer (hence a bias):
+ *
+ *     y = (1/l) * sum_i (x . S_i) . U_i + b
+ *
+ * S_i (in x k) are fixed random sketches, U_i (k x out) learned factors.  The
+ * library takes the l terms concatenated:
+ *
+ *     S_cat [in, R]   column i*k + j  = column j of S_i         (R = l*k)
+ *     U_cat [R, out]  rows   i*k .. i*k+k-1 = U_i
+ *
+ * so that  y = (1/l) * (x . S_cat) . U_cat + b.
+ *
+ * Common rules for the three compute entry points
+ *   - Every pointer is a DEVICE pointer, 16-byte aligned, to a dense row-major
+ *     array with no padding (leading dimension = last dimension).
+ *   - `dtype` is the storage type of x, S_cat, U_cat, bias, y, dY and dX
+ *     (SK_F32, or SK_BF16 with fp32 accumulation).  dU_cat and dbias are
+ *     always fp32.
+ *   - tokens >= 1 (any value); in, out and R = l*k must be positive multiples
+ *     of 16, l >= 1, k >= 1.
+ *   - The caller owns every buffer, the workspace included.  The library
+ *     allocates nothing, keeps no state between calls, and never synchronises:
+ *     all work is enqueued on `stream` (a hipStream_t; NULL = default stream).
+ *     Outputs are overwritten, not accumulated into.  Inputs and outputs must
+ *     not overlap.  `workspace` must hold at least
+ *     sk_linear_workspace_bytes(op, ...) bytes (it may be NULL when that is 0)
+ *     and its contents are undefined after the call.
+ *   - The intermediate x . S_cat is never kept between calls: the backward
+ *     pass for the factors recomputes it.
+ *   - Return value: SK_OK, or an error code; nothing is thrown across the ABI.
+ *     Arguments are validated before any HIP call is made, so a bad call
+ *     returns SK_ERR_INVALID_ARG / SK_ERR_UNSUPPORTED / SK_ERR_WORKSPACE with
+ *     no GPU work enqueued (and also on a machine with no GPU).
+ */
+#ifndef SK_H
+#define SK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SK_OK = 0,
+  SK_ERR_INVALID_ARG = 1, /* null required pointer, misaligned pointer, non-positive size */
+  SK_ERR_UNSUPPORTED = 2, /* unknown dtype/op, or in/out/R not a multiple of 16 */
+  SK_ERR_WORKSPACE = 3,   /* workspace missing or smaller than required */
+  SK_ERR_HIP = 4          /* a HIP call failed; see sk_last_hip_error() */
+} sk_status;
+
+typedef enum { SK_F32 = 0, SK_BF16 = 1 } sk_dtype;
+
+typedef enum { SK_OP_FWD = 0, SK_OP_BWD_INPUT = 1, SK_OP_BWD_WEIGHT = 2 } sk_op;
+
+/*
+ * Forward (Sec. 3.1):  y = (1/l) * (x . S_cat) . U_cat + bias.
+ *   x [tokens, in], S_cat [in, R], U_cat [R, out], bias [out] or NULL (no bias),
+ *   y [tokens, out] (output, storage type `dtype`).
+ * In bf16 the R-wide intermediate is rounded to bf16 once, between the two
+ * contractions; scaling and bias are applied in fp32 before y is rounded.
+ */
+sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, const void* bias,
+                        void* y, int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                        sk_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Gradient with respect to the input (the exact derivative of the forward of
+ * Sec. 3.1; the paper prints no formula):
+ *     dX = (1/l) * (dY . U_cat^T) . S_cat^T
+ *   dY [tokens, out], S_cat [in, R], U_cat [R, out], dX [tokens, in] (output).
+ */
+sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_cat, void* dX,
+                              int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                              sk_dtype dtype, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/*
+ * Gradient with respect to the learned factors and the bias (exact derivative
+ * of the forward of Sec. 3.1):
+ *     dU_cat = (1/l) * (x . S_cat)^T . dY          (rows i*k.. are dU_i)
+ *     dbias  = sum over tokens of dY
+ *   x [tokens, in], S_cat [in, R], dY [tokens, out],
+ *   dU_cat [R, out] fp32 (output), dbias [out] fp32 (output) or NULL (skipped).
+ * x . S_cat is recomputed here (into the workspace), not read from a saved
+ * copy.  The reduction over tokens uses a fixed order: results are
+ * bit-reproducible from run to run for the same shapes.
+ */
+sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY, float* dU_cat,
+                               float* dbias, int64_t tokens, int64_t in, int64_t out, int32_t l,
+                               int32_t k, sk_dtype dtype, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/*
+ * Bytes of workspace that `op` needs for these sizes (0 when it needs none).
+ * Returns (size_t)-1 for arguments the compute call would reject.
+ */
+size_t sk_linear_workspace_bytes(sk_op op, int64_t tokens, int64_t in, int64_t out, int32_t l,
+                                 int32_t k, sk_dtype dtype);
+
+/* Static, human-readable name of a status code. */
+const char* sk_status_string(sk_status status);
+
+/* Text of the HIP error behind the calling thread's last SK_ERR_HIP ("" if none). */
+const char* sk_last_hip_error(void);
+
+/*
+ * Tuning/testing knob, process-wide (not part of the layer's definition):
+ * which kernel plan the three entry points pick.
+ *   0 = automatic (default): per-shape choice;
+ *   1 = force the fused plan (intermediate kept on chip) where the shape
+ *       allows it, i.e. bf16 with R <= 512;
+ *   2 = force the two-pass plan (intermediate through the workspace).
+ * sk_linear_workspace_bytes reports the maximum over the plans, so a workspace
+ * sized by it serves whatever is selected.  Returns the previous value, or -1
+ * (and changes nothing) for a value out of range.
+ */
+int sk_set_plan(int plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SK_H */

@@ -1,0 +1,291 @@
+// libsk's C ABI (include/sk.h): argument validation, per-shape plan, launches.
+// Validation runs before any HIP call, so error paths work without a GPU.
+#include <atomic>
+#include <cstring>
+#include <string>
+
+#include "../../include/sk.h"
+#include "sk_launch.h"
+
+namespace {
+
+using namespace sk;
+
+constexpr int NUM_CUS = 256;
+constexpr size_t WS_ALIGN = 256;
+
+thread_local std::string g_hip_error;
+std::atomic<int> g_plan{0};
+
+size_t align_up(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+
+sk_status hip_fail(hipError_t e, const char* what) {
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return SK_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Shape {
+  int64_t T, in, out;
+  int l, k, R;
+  sk_dtype dtype;
+  size_t esize;
+};
+
+// Checks everything that does not involve pointers.
+sk_status check_shape(int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                      sk_dtype dtype, Shape& s) {
+  if (tokens < 1 || in < 1 || out < 1 || l < 1 || k < 1) return SK_ERR_INVALID_ARG;
+  if (dtype != SK_F32 && dtype != SK_BF16) return SK_ERR_UNSUPPORTED;
+  const int64_t R = (int64_t)l * k;
+  if ((in & 15) || (out & 15) || (R & 15)) return SK_ERR_UNSUPPORTED;
+  // index arithmetic inside the kernels is 32-bit per dimension
+  if (tokens > (1 << 24) || in > (1 << 20) || out > (1 << 20) || R > (1 << 16))
+    return SK_ERR_UNSUPPORTED;
+  s.T = tokens; s.in = in; s.out = out; s.l = l; s.k = k; s.R = (int)R; s.dtype = dtype;
+  s.esize = dtype == SK_BF16 ? 2 : 4;
+  return SK_OK;
+}
+
+// Largest tile that still gives every CU a work-group, without tiles that are
+// mostly padding; the smallest fitting tile when the problem cannot fill the chip.
+int choose_tile(int64_t M, int64_t N, int splits) {
+  const int64_t m_cap = (M + 63) / 64 * 64, n_cap = (N + 63) / 64 * 64;
+  int best = TILE_64x64;
+  for (int t = 0; t < TILE_COUNT; ++t) {
+    int bm, bn;
+    tile_dims(t, bm, bn);
+    if (bm > m_cap || bn > n_cap) continue;
+    const int64_t wgs = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * splits;
+    if (wgs >= NUM_CUS) return t;
+  }
+  return best;
+}
+
+struct WeightPlan {
+  int tile;
+  int splits;
+  int k_per_split;
+  size_t z_bytes, part_bytes, csum_bytes;
+  size_t total() const { return z_bytes + part_bytes + csum_bytes; }
+};
+
+// Split of the token contraction of dU = Z^T . dY: enough work-groups to fill the
+// chip, at least 256 tokens per split, splits in a fixed order (deterministic sum).
+WeightPlan plan_weight(const Shape& s) {
+  WeightPlan w{};
+  int bm, bn;
+  if (s.dtype == SK_BF16) {
+    // the output (R x out) is small: prefer small tiles and few splits, since every
+    // split writes and re-reads a full fp32 slab of it
+    w.tile = (s.R >= 128 && s.out >= 128 && ((s.R + 127) / 128) * ((s.out + 127) / 128) >= NUM_CUS)
+                 ? TILE_128x128 : TILE_64x64;
+    tile_dims(w.tile, bm, bn);
+  } else {
+    w.tile = -1;
+    bm = F32_BM; bn = F32_BN;
+  }
+  const int64_t tiles = ((s.R + bm - 1) / bm) * ((s.out + bn - 1) / bn);
+  int64_t splits = (2 * NUM_CUS + tiles - 1) / tiles;
+  const int64_t max_splits = (s.T + 255) / 256;
+  if (splits > max_splits) splits = max_splits;
+  if (splits > 64) splits = 64;
+  if (splits < 1) splits = 1;
+  int64_t kps = (s.T + splits - 1) / splits;
+  kps = (kps + 63) / 64 * 64;
+  splits = (s.T + kps - 1) / kps;
+  w.splits = (int)splits;
+  w.k_per_split = (int)kps;
+  w.z_bytes = align_up((size_t)s.T * s.R * s.esize);
+  w.part_bytes = splits > 1 ? align_up((size_t)splits * s.R * s.out * 4) : 0;
+  w.csum_bytes = splits > 1 ? align_up((size_t)splits * s.out * 4) : 0;
+  return w;
+}
+
+bool use_chain(const Shape& s) {
+  const int plan = g_plan.load(std::memory_order_relaxed);
+  if (s.dtype != SK_BF16 || !chain_supported(s.R) || plan == 2) return false;
+  if (plan == 1) return true;
+  return false;  // automatic choice: two-pass until the fused plan is measured faster
+}
+
+size_t workspace_for(sk_op op, const Shape& s) {
+  const size_t mid = align_up((size_t)s.T * s.R * s.esize);  // Z or G
+  switch (op) {
+    case SK_OP_FWD:
+    case SK_OP_BWD_INPUT:
+      return mid;  // the fused plan needs none; report the maximum over plans
+    case SK_OP_BWD_WEIGHT:
+      return plan_weight(s).total();
+  }
+  return 0;
+}
+
+hipError_t gemm(const Shape& s, GemmKind kind, GemmArgs a, hipStream_t st) {
+  if (s.dtype == SK_BF16) return launch_gemm_bf16(kind, choose_tile(a.M, a.N, 1), a, st);
+  return launch_gemm_f32(kind, a, st);
+}
+
+// C[M,N] = scale * (A[M,K] . B) + bias through the workspace-free single GEMM.
+GemmArgs dense_args(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                    int64_t M, int64_t N, int64_t K, float scale, const void* bias) {
+  GemmArgs a{};
+  a.A = A; a.B = B; a.C = C; a.bias = bias; a.colsum = nullptr;
+  a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+  a.M = (int)M; a.N = (int)N; a.K = (int)K;
+  a.k_per_split = (int)((K + 63) / 64 * 64);
+  a.splits = 1;
+  a.scale = scale;
+  return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sk_status_string(sk_status status) {
+  switch (status) {
+    case SK_OK: return "SK_OK";
+    case SK_ERR_INVALID_ARG: return "SK_ERR_INVALID_ARG: null or misaligned pointer, or non-positive size";
+    case SK_ERR_UNSUPPORTED: return "SK_ERR_UNSUPPORTED: unknown dtype/op, or in/out/l*k not a multiple of 16";
+    case SK_ERR_WORKSPACE: return "SK_ERR_WORKSPACE: workspace missing or too small";
+    case SK_ERR_HIP: return "SK_ERR_HIP: a HIP call failed (see sk_last_hip_error)";
+  }
+  return "unknown sk_status";
+}
+
+const char* sk_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int sk_set_plan(int plan) {
+  if (plan < 0 || plan > 2) return -1;
+  return g_plan.exchange(plan);
+}
+
+size_t sk_linear_workspace_bytes(sk_op op, int64_t tokens, int64_t in, int64_t out, int32_t l,
+                                 int32_t k, sk_dtype dtype) {
+  Shape s;
+  if (op != SK_OP_FWD && op != SK_OP_BWD_INPUT && op != SK_OP_BWD_WEIGHT) return (size_t)-1;
+  if (check_shape(tokens, in, out, l, k, dtype, s) != SK_OK) return (size_t)-1;
+  return workspace_for(op, s);
+}
+
+sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, const void* bias,
+                        void* y, int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                        sk_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !S_cat || !U_cat || !y) return SK_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(S_cat) || !aligned16(U_cat) || !aligned16(y) ||
+      !aligned16(bias) || !aligned16(workspace))
+    return SK_ERR_INVALID_ARG;
+  Shape s;
+  const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
+  if (st != SK_OK) return st;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const float scale = 1.0f / (float)l;
+  g_hip_error.clear();
+
+  if (use_chain(s)) {
+    ChainArgs c{};
+    c.A = x; c.B1 = S_cat; c.B2 = U_cat; c.bias = bias; c.C = y;
+    c.lda = in; c.ldb1 = s.R; c.ldb2 = out; c.ldc = out;
+    c.M = (int)tokens; c.K1 = (int)in; c.R = s.R; c.N = (int)out; c.scale = scale;
+    const hipError_t e = launch_chain_bf16(false, c, hs);
+    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_fwd (fused)");
+  }
+  const size_t need = align_up((size_t)s.T * s.R * s.esize);
+  if (!workspace || workspace_bytes < need) return SK_ERR_WORKSPACE;
+  // Z = x . S_cat, then y = scale * Z . U_cat + bias
+  hipError_t e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (x.S)");
+  e = gemm(s, GEMM_NN, dense_args(workspace, s.R, U_cat, out, y, out, tokens, out, s.R, scale, bias), hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (Z.U)");
+  return SK_OK;
+}
+
+sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_cat, void* dX,
+                              int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                              sk_dtype dtype, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!dY || !S_cat || !U_cat || !dX) return SK_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(S_cat) || !aligned16(U_cat) || !aligned16(dX) ||
+      !aligned16(workspace))
+    return SK_ERR_INVALID_ARG;
+  Shape s;
+  const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
+  if (st != SK_OK) return st;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const float scale = 1.0f / (float)l;
+  g_hip_error.clear();
+
+  if (use_chain(s)) {
+    ChainArgs c{};
+    c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
+    c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
+    c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
+    const hipError_t e = launch_chain_bf16(true, c, hs);
+    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd_input (fused)");
+  }
+  const size_t need = align_up((size_t)s.T * s.R * s.esize);
+  if (!workspace || workspace_bytes < need) return SK_ERR_WORKSPACE;
+  // G = dY . U_cat^T (U_cat read as [N = R, K = out]), then dX = scale * G . S_cat^T
+  hipError_t e = gemm(s, GEMM_NT, dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr), hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_input (dY.U^T)");
+  e = gemm(s, GEMM_NT, dense_args(workspace, s.R, S_cat, s.R, dX, in, tokens, in, s.R, scale, nullptr), hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_input (G.S^T)");
+  return SK_OK;
+}
+
+sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY, float* dU_cat,
+                               float* dbias, int64_t tokens, int64_t in, int64_t out, int32_t l,
+                               int32_t k, sk_dtype dtype, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  if (!x || !S_cat || !dY || !dU_cat) return SK_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(S_cat) || !aligned16(dY) || !aligned16(dU_cat) ||
+      !aligned16(dbias) || !aligned16(workspace))
+    return SK_ERR_INVALID_ARG;
+  Shape s;
+  const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
+  if (st != SK_OK) return st;
+  const WeightPlan w = plan_weight(s);
+  if (!workspace || workspace_bytes < w.total()) return SK_ERR_WORKSPACE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const float scale = 1.0f / (float)l;
+  g_hip_error.clear();
+
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  void* Z = ws;
+  float* part = reinterpret_cast<float*>(ws + w.z_bytes);
+  float* cpart = reinterpret_cast<float*>(ws + w.z_bytes + w.part_bytes);
+
+  // Z = x . S_cat, recomputed here rather than kept from the forward pass
+  hipError_t e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (x.S)");
+
+  // dU = scale * Z^T . dY and db = column sums of dY, the token axis split in order
+  GemmArgs a{};
+  a.A = Z; a.B = dY; a.lda = s.R; a.ldb = out; a.ldc = out;
+  a.M = s.R; a.N = (int)out; a.K = (int)tokens;
+  a.splits = w.splits; a.k_per_split = w.k_per_split;
+  a.bias = nullptr;
+  if (w.splits == 1) {
+    a.C = dU_cat; a.colsum = dbias; a.scale = scale;
+  } else {
+    a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
+  }
+  e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_TN_F32, w.tile, a, hs)
+                         : launch_gemm_f32(GEMM_TN_F32, a, hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (Z^T.dY)");
+  if (w.splits > 1) {
+    ReduceArgs r{part, dU_cat, (int64_t)s.R * out, w.splits, scale};
+    e = launch_reduce_splits(r, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (reduce dU)");
+    if (dbias) {
+      ReduceArgs rb{cpart, dbias, out, w.splits, 1.0f};
+      e = launch_reduce_splits(rb, hs);
+      if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (reduce db)");
+    }
+  }
+  return SK_OK;
+}
+
+}  // extern "C"

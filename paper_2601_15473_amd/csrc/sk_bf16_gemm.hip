@@ -1,0 +1,244 @@
+// bf16 MFMA GEMM with fp32 accumulation for gfx950: the contraction every
+// two-pass plan of the SKLinear forward/backward is made of.
+//
+//   C[M, N] = scale * (A . B) (+ bias[n]),   or raw fp32 split-K partial slabs.
+//
+// One work-group of 256 threads (4 waves, 2 x 2) owns a BM x BN tile; each wave
+// a (BM/2) x (BN/2) sub-tile of 32x32 MFMA blocks.  Operands go global ->
+// registers -> LDS (double buffered, one barrier per 64-wide k chunk) and are
+// read from LDS directly in the MFMA fragment layout; operands whose contiguous
+// dimension is not k are read with the LDS transpose read.  The result tile is
+// re-laid out through LDS so that global stores are whole contiguous rows.
+#include "sk_bf16_tile.h"
+#include "sk_launch.h"
+
+namespace sk {
+
+template <typename OutT> struct OutTraits;
+template <> struct OutTraits<bf16> { static constexpr int PIECE = 8; };    // 4 bf16
+template <> struct OutTraits<float> { static constexpr int PIECE = 16; };  // 4 fp32
+
+template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
+  typedef OpTile<BM, A_KC> TA;
+  typedef OpTile<BN, B_KC> TB;
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int STAGE = TA::ELEMS + TB::ELEMS;
+  constexpr int PIECE = OutTraits<OutT>::PIECE;
+  constexpr int EP_LD = WN * (int)sizeof(OutT) + PIECE;  // bytes per staged output row
+  constexpr int EP_BYTES = 4 * 32 * EP_LD;
+  constexpr int LDS_BYTES = (2 * STAGE * 2 > EP_BYTES) ? 2 * STAGE * 2 : EP_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+  bf16* const lds = reinterpret_cast<bf16*>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int tiles = p.tiles_m * p.tiles_n;
+  const int id = xcd_remap(blockIdx.x, tiles * p.splits);
+  const int split = id / tiles;
+  int tile_m, tile_n;
+  tile_coords(id - split * tiles, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int k_begin = split * p.k_per_split;
+  const int k_end = (k_begin + p.k_per_split < p.K) ? k_begin + p.k_per_split : p.K;
+  const int nk = (k_end - k_begin + BK - 1) / BK;
+
+  const bf16* __restrict__ A = static_cast<const bf16*>(p.A);
+  const bf16* __restrict__ B = static_cast<const bf16*>(p.B);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  f32x16 csum[COLSUM ? TN : 1];
+  if (COLSUM) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) csum[j][r] = 0.f;
+  }
+  // Column sums of B ride on the MFMA: an all-ones fragment in place of A's.
+  const bool do_colsum = COLSUM && p.colsum != nullptr && tile_m == 0 && wm == 0;
+  bf16x8 ones;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ones[j] = (bf16)1.0f;
+
+  uint4 ra[TA::PIECES], rb[TB::PIECES];
+  if (nk > 0) {
+    TA::load(ra, A, p.lda, m0, p.M, k_begin, k_end, tid);
+    TB::load(rb, B, p.ldb, n0, p.N, k_begin, k_end, tid);
+    TA::store(lds, ra, tid);
+    TB::store(lds + TA::ELEMS, rb, tid);
+  }
+  __syncthreads();
+
+  for (int kc = 0; kc < nk; ++kc) {
+    const bf16* As = lds + (kc & 1) * STAGE;
+    const bf16* Bs = As + TA::ELEMS;
+    const bool more = kc + 1 < nk;
+    if (more) {
+      const int k0 = k_begin + (kc + 1) * BK;
+      TA::load(ra, A, p.lda, m0, p.M, k0, k_end, tid);
+      TB::load(rb, B, p.ldb, n0, p.N, k0, k_end, tid);
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = read_frag<A_KC, TA::LD>(As, wm * WM + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = read_frag<B_KC, TB::LD>(Bs, wn * WN + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+      if (COLSUM) {
+        if (do_colsum) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            csum[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], ones, csum[j], 0, 0, 0);
+        }
+      }
+    }
+    if (more) {
+      bf16* An = lds + ((kc + 1) & 1) * STAGE;
+      TA::store(An, ra, tid);
+      TB::store(An + TA::ELEMS, rb, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulators -> per-wave LDS staging -> contiguous row stores ----
+  // Lane l owns output row l % 32 of each 32-row block and, for q = 0..3, the four
+  // columns 8 q + 4 (l / 32) .. +3 of each 32-column block.
+  unsigned char* const stage = smem + wave * (32 * EP_LD);
+  OutT* __restrict__ C = static_cast<OutT*>(p.C) +
+                         (sizeof(OutT) == 4 ? (int64_t)split * p.M * p.ldc : (int64_t)0);
+  const bf16* __restrict__ bias = static_cast<const bf16*>(p.bias);
+  const float scale = p.scale;
+  const int wn0 = n0 + wn * WN;  // first global column of this wave
+  constexpr int PPR = WN * (int)sizeof(OutT) / PIECE;  // pieces per staged row
+
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = j * 32 + q * 8 + (lane >> 5) * 4;  // column inside the wave tile
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e] * scale;
+        if (sizeof(OutT) == 2) {
+          if (bias != nullptr && wn0 + c < p.N) {
+            const uint2 bb = *reinterpret_cast<const uint2*>(bias + wn0 + c);
+            v[0] += bf16_bits_to_float(bb.x & 0xffffu);
+            v[1] += bf16_bits_to_float(bb.x >> 16);
+            v[2] += bf16_bits_to_float(bb.y & 0xffffu);
+            v[3] += bf16_bits_to_float(bb.y >> 16);
+          }
+          uint2 w;
+          w.x = pack_bf16x2(v[0], v[1]);
+          w.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(stage + (lane & 31) * EP_LD + c * 2) = w;
+        } else {
+          *reinterpret_cast<float4*>(stage + (lane & 31) * EP_LD + c * 4) =
+              make_float4(v[0], v[1], v[2], v[3]);
+        }
+      }
+    }
+    __syncthreads();
+    const int row_base = m0 + wm * WM + i * 32;
+#pragma unroll
+    for (int it = 0; it < (32 * PPR) / 64; ++it) {
+      const int idx = it * 64 + lane;
+      const int r = idx / PPR, pc = idx % PPR;
+      const int gm = row_base + r, gn = wn0 + pc * 4;
+      if (gm < p.M && gn < p.N) {
+        if (sizeof(OutT) == 2) {
+          const uint2 w = *reinterpret_cast<const uint2*>(stage + r * EP_LD + pc * PIECE);
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(C) + (int64_t)gm * p.ldc + gn) = w;
+        } else {
+          const float4 w = *reinterpret_cast<const float4*>(stage + r * EP_LD + pc * PIECE);
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)gm * p.ldc + gn) = w;
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (COLSUM) {
+    // every D column of csum holds the same sums; lanes 0 and 32 write them out
+    if (do_colsum && (lane & 31) == 0) {
+      float* out = p.colsum + (int64_t)split * p.N;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int gn = wn0 + j * 32 + q * 8 + (lane >> 5) * 4;
+          if (gn < p.N)
+            *reinterpret_cast<float4*>(out + gn) = make_float4(
+                csum[j][q * 4 + 0], csum[j][q * 4 + 1], csum[j][q * 4 + 2], csum[j][q * 4 + 3]);
+        }
+    }
+  }
+}
+
+// out[i] = scale * sum over splits of part[s][i], splits added in index order.
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const ReduceArgs p) {
+  const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 >= p.n) return;
+  float4 s = *reinterpret_cast<const float4*>(p.part + i4);
+  for (int k = 1; k < p.splits; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(p.part + (int64_t)k * p.n + i4);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  s.x *= p.scale; s.y *= p.scale; s.z *= p.scale; s.w *= p.scale;
+  *reinterpret_cast<float4*>(p.out + i4) = s;
+}
+
+template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
+static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
+  a.tiles_m = (a.M + BM - 1) / BM;
+  a.tiles_n = (a.N + BN - 1) / BN;
+  const long long grid = (long long)a.tiles_m * a.tiles_n * a.splits;
+  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, A_KC, B_KC, OutT, COLSUM>), dim3((unsigned)grid),
+                     dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+template <bool A_KC, bool B_KC, typename OutT, bool COLSUM>
+static hipError_t launch_tiles(int tile, const GemmArgs& a, hipStream_t s) {
+  switch (tile) {
+    case TILE_256x256: return launch_cfg<256, 256, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_128x128: return launch_cfg<128, 128, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_128x64: return launch_cfg<128, 64, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_64x128: return launch_cfg<64, 128, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_64x64: return launch_cfg<64, 64, A_KC, B_KC, OutT, COLSUM>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStream_t s) {
+  switch (kind) {
+    case GEMM_NN: return launch_tiles<true, false, bf16, false>(tile, a, s);
+    case GEMM_NT: return launch_tiles<true, true, bf16, false>(tile, a, s);
+    case GEMM_TN_F32: return launch_tiles<false, false, float, true>(tile, a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s) {
+  const int64_t groups = (a.n / 4 + 255) / 256;
+  if (groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)groups), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace sk

@@ -1,0 +1,71 @@
+// Shared declarations of libsk's HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sk {
+
+typedef __bf16 bf16;
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// How a GEMM result tile leaves the kernel.
+enum Epilogue : int {
+  EPI_STORE = 0,    // C = scale * acc (+ bias[n]), rounded to the storage type
+  EPI_PARTIAL = 1,  // split-K: raw fp32 partial sums, one [M, N] slab per split
+};
+
+// C[M, N] = A . B over k in [0, K), optionally split over blockIdx-derived k ranges.
+//   a_kc: A is stored [M, K] (k contiguous); otherwise [K, M] (m contiguous)
+//   b_kc: B is stored [N, K] (k contiguous); otherwise [K, N] (n contiguous)
+// lda/ldb/ldc are row strides in elements of the stored arrays.
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;             // storage type (EPI_STORE) or fp32 partial slabs (EPI_PARTIAL)
+  const void* bias;    // [N] storage type, or null (EPI_STORE only)
+  float* colsum;       // [splits, N] fp32 sums of B over k, or null (EPI_PARTIAL only)
+  int64_t lda, ldb, ldc;
+  int M, N, K;
+  int k_per_split;     // multiple of the kernel's k chunk; K when not split
+  int splits;
+  int tiles_m, tiles_n;
+  float scale;
+};
+
+// out[i] = scale * sum_s part[s][i] for i < n, in split order (deterministic).
+struct ReduceArgs {
+  const float* part;
+  float* out;
+  int64_t n;           // elements per slab
+  int splits;
+  float scale;
+};
+
+// XCD-aware work-group order.  Work-groups are handed to the 8 XCDs round-robin,
+// so consecutive hardware ids land on different L2s.  Remap so that each XCD
+// gets one contiguous run of logical tile ids (neighbouring tiles share operand
+// panels in that XCD's L2).
+__device__ __forceinline__ int xcd_remap(int hw_id, int total) {
+  const int per = total >> 3;
+  if (hw_id >= (per << 3)) return hw_id;
+  return (hw_id & 7) * per + (hw_id >> 3);
+}
+
+// Logical tile id -> (tile_m, tile_n): bands of 8 tile rows, walked row-first
+// inside a band, so a run of ids covers a compact block of the output.
+__device__ __forceinline__ void tile_coords(int id, int tiles_m, int tiles_n, int& tm, int& tn) {
+  constexpr int GM = 8;
+  const int band_sz = GM * tiles_n;
+  const int band = id / band_sz;
+  const int first_m = band * GM;
+  const int rows = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in_band = id - band * band_sz;
+  tm = first_m + in_band % rows;
+  tn = in_band / rows;
+}
+
+}  // namespace sk

@@ -1,0 +1,56 @@
+// Host-side launchers of libsk's kernels (internal; the public ABI is include/sk.h).
+#pragma once
+#include "sk_common.h"
+
+namespace sk {
+
+enum GemmKind : int {
+  GEMM_NN = 0,      // A [M,K], B [K,N]            -> storage type
+  GEMM_NT = 1,      // A [M,K], B [N,K]            -> storage type
+  GEMM_TN_F32 = 2,  // A [K,M], B [K,N], split-K   -> fp32 (+ column sums of B)
+};
+
+enum TileCfg : int {
+  TILE_256x256 = 0,
+  TILE_128x128 = 1,
+  TILE_128x64 = 2,
+  TILE_64x128 = 3,
+  TILE_64x64 = 4,
+  TILE_COUNT = 5,
+};
+
+inline void tile_dims(int tile, int& bm, int& bn) {
+  static const int dims[TILE_COUNT][2] = {{256, 256}, {128, 128}, {128, 64}, {64, 128}, {64, 64}};
+  bm = dims[tile][0];
+  bn = dims[tile][1];
+}
+
+// bf16 operands, fp32 accumulation (MFMA).  `tiles_m/tiles_n` of `a` are filled in here.
+hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStream_t s);
+// fp32 operands and accumulation (MFMA), one tile shape.
+hipError_t launch_gemm_f32(GemmKind kind, const GemmArgs& a, hipStream_t s);
+constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16;
+
+hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s);
+
+// Fused two-stage chain for bf16 with the R-wide intermediate kept in LDS:
+//   C[M, N] = scale * ((A . B1) rounded to bf16) . B2 (+ bias),  R <= 512.
+//   b_kc = false: B1 [K1, R], B2 [R, N]   (forward:      x, S_cat, U_cat)
+//   b_kc = true : B1 [R, K1], B2 [N, R]   (input grad:   dY, U_cat, S_cat)
+struct ChainArgs {
+  const void* A;       // [M, K1]
+  const void* B1;
+  const void* B2;
+  const void* bias;    // [N] or null
+  void* C;             // [M, N]
+  int64_t lda, ldb1, ldb2, ldc;
+  int M, K1, R, N;
+  int n_slices;        // the N range is cut into this many slices, one per work-group column
+  int tiles_m;
+  float scale;
+};
+bool chain_supported(int R);
+int chain_bm(int R);
+hipError_t launch_chain_bf16(bool b_kc, const ChainArgs& a, hipStream_t s);
+
+}  // namespace sk

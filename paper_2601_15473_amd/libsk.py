@@ -1,0 +1,116 @@
+"""ctypes binding of libsk.so: the entry points of include/sk.h under the same
+names.  Argument marshalling only -- every step of the computation runs in the
+library's HIP kernels.  There is no CPU fallback: if the library has not been
+built (``python -m paper_2601_15473_amd.build``) importing this module fails.
+
+Pointer arguments may be given as integers (device addresses), objects with a
+``data_ptr()`` method (torch tensors) or None.  ``stream`` may be an integer
+handle, an object with a ``cuda_stream`` attribute (torch.cuda.Stream) or None
+for the default stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libsk.so")
+
+SK_OK, SK_ERR_INVALID_ARG, SK_ERR_UNSUPPORTED, SK_ERR_WORKSPACE, SK_ERR_HIP = range(5)
+SK_F32, SK_BF16 = 0, 1
+SK_OP_FWD, SK_OP_BWD_INPUT, SK_OP_BWD_WEIGHT = 0, 1, 2
+DTYPES = {"f32": SK_F32, "bf16": SK_BF16}
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2601_15473_amd.build` "
+        "(there is no fallback implementation)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _i32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+_tail = [_i64, _i64, _i64, _i32, _i32, ctypes.c_int, _vp, _sz, _vp]
+
+_lib.sk_linear_fwd.restype = ctypes.c_int
+_lib.sk_linear_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp] + _tail
+_lib.sk_linear_bwd_input.restype = ctypes.c_int
+_lib.sk_linear_bwd_input.argtypes = [_vp, _vp, _vp, _vp] + _tail
+_lib.sk_linear_bwd_weight.restype = ctypes.c_int
+_lib.sk_linear_bwd_weight.argtypes = [_vp, _vp, _vp, _vp, _vp] + _tail
+_lib.sk_linear_workspace_bytes.restype = _sz
+_lib.sk_linear_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, _i64, _i32, _i32, ctypes.c_int]
+_lib.sk_status_string.restype = ctypes.c_char_p
+_lib.sk_status_string.argtypes = [ctypes.c_int]
+_lib.sk_last_hip_error.restype = ctypes.c_char_p
+_lib.sk_last_hip_error.argtypes = []
+_lib.sk_set_plan.restype = ctypes.c_int
+_lib.sk_set_plan.argtypes = [ctypes.c_int]
+
+EXPORTS = ("sk_linear_fwd", "sk_linear_bwd_input", "sk_linear_bwd_weight",
+           "sk_linear_workspace_bytes", "sk_status_string", "sk_last_hip_error", "sk_set_plan")
+
+
+class SkError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        msg = sk_status_string(status)
+        if status == SK_ERR_HIP:
+            msg += " -- " + sk_last_hip_error()
+        super().__init__(msg)
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    return a.data_ptr()
+
+
+def _stream(s):
+    if s is None or isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def sk_linear_fwd(x, S_cat, U_cat, bias, y, tokens, d_in, d_out, l, k, dtype,
+                  workspace, workspace_bytes, stream=None):
+    return _lib.sk_linear_fwd(_ptr(x), _ptr(S_cat), _ptr(U_cat), _ptr(bias), _ptr(y),
+                              tokens, d_in, d_out, l, k, dtype,
+                              _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def sk_linear_bwd_input(dY, S_cat, U_cat, dX, tokens, d_in, d_out, l, k, dtype,
+                        workspace, workspace_bytes, stream=None):
+    return _lib.sk_linear_bwd_input(_ptr(dY), _ptr(S_cat), _ptr(U_cat), _ptr(dX),
+                                    tokens, d_in, d_out, l, k, dtype,
+                                    _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def sk_linear_bwd_weight(x, S_cat, dY, dU_cat, dbias, tokens, d_in, d_out, l, k, dtype,
+                         workspace, workspace_bytes, stream=None):
+    return _lib.sk_linear_bwd_weight(_ptr(x), _ptr(S_cat), _ptr(dY), _ptr(dU_cat), _ptr(dbias),
+                                     tokens, d_in, d_out, l, k, dtype,
+                                     _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def sk_linear_workspace_bytes(op, tokens, d_in, d_out, l, k, dtype):
+    return _lib.sk_linear_workspace_bytes(op, tokens, d_in, d_out, l, k, dtype)
+
+
+def sk_status_string(status):
+    return _lib.sk_status_string(status).decode()
+
+
+def sk_last_hip_error():
+    return _lib.sk_last_hip_error().decode()
+
+
+def sk_set_plan(plan):
+    return _lib.sk_set_plan(plan)
+
+
+def check(status):
+    """Raise SkError unless ``status`` is SK_OK."""
+    if status != SK_OK:
+        raise SkError(status)

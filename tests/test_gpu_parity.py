@@ -1,0 +1,166 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle, on the GPU.
+
+Bar: max relative error (tests/skgpu.rel_err) <= 1e-4 for fp32 and <= 2e-2 for
+bf16 storage with fp32 accumulation -- the tolerances stated for this layer.
+The oracle sees the same stored (already rounded) inputs, widened to fp64.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sklinear as O
+from paper_2601_15473_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+from skgpu import TOL, DeviceLayer, rel_err, to_f64  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def sk():
+    from paper_2601_15473_amd import libsk
+    yield libsk
+    libsk.sk_set_plan(0)
+
+
+def oracle_all(t: W.Tensors):
+    v = {n: a.astype(np.float64) for n, a in t.value.items()}
+    b = v.get("b")
+    return dict(
+        y=O.forward(v["x"], v["S"], v["U"], b),
+        dX=O.grad_input(v["dY"], v["S"], v["U"]),
+        dU=O.grad_factors(v["x"], v["S"], v["dY"]).reshape(t.workload.R, t.workload.d_out),
+        db=O.grad_bias(v["dY"]),
+    )
+
+
+def check_all(sk, w: W.Workload, plan: int, with_bias=True):
+    print(f"case {w.name} T={w.tokens} in={w.d_in} out={w.d_out} l={w.l} k={w.k} "
+          f"{w.dtype} plan={plan} bias={with_bias}", flush=True)
+    sk.sk_set_plan(plan)
+    t = W.generate(w, with_bias=with_bias)
+    dev = DeviceLayer(t, sk)
+    dev.run_all()
+    want = oracle_all(t)
+    got = dict(y=to_f64(dev.y), dX=to_f64(dev.dX), dU=to_f64(dev.dU), db=to_f64(dev.db))
+    errs = {n: rel_err(got[n], want[n]) for n in want}
+    print("   errors:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= TOL[w.dtype], (n, e)
+    return errs
+
+
+SMALL = [
+    W.TINY,                                                         # config 0 as stated
+    W.Workload("f32_ragged", 77, 48, 80, 3, 16, "f32", seed=1),
+    W.Workload("f32_multi_tile", 200, 144, 208, 2, 40, "f32", seed=2),
+    W.Workload("bf16_one_token", 1, 64, 48, 1, 16, "bf16", seed=3),
+    W.Workload("bf16_ragged", 333, 208, 176, 3, 16, "bf16", seed=4),
+    W.Workload("bf16_r16", 130, 96, 112, 1, 16, "bf16", seed=5),
+    W.scaled(W.BERT_BASE_FFN_UP, tokens=1000),
+    W.scaled(W.BERT_LARGE_FFN_UP, tokens=600),
+    W.scaled(W.BERT_LARGE_FFN_DOWN, tokens=600),
+    W.scaled(W.LLM_MLP, tokens=300),
+] + [W.scaled(w, tokens=700) for w in W.BERT_BASE_PROJ]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("plan", [2, 1], ids=["two_pass", "fused"])
+def test_parity_small(sk, w, plan):
+    check_all(sk, w, plan)
+
+
+@pytest.mark.parametrize("plan", [2, 1], ids=["two_pass", "fused"])
+def test_no_bias_and_no_dbias(sk, plan):
+    w = W.Workload("bf16_nobias", 150, 128, 96, 2, 32, "bf16", seed=6)
+    check_all(sk, w, plan, with_bias=False)
+    t = W.generate(w)
+    dev = DeviceLayer(t, sk)
+    sk.check(dev.bwd_weight(with_db=False))
+    torch.cuda.synchronize()
+    assert torch.isnan(dev.db).all()          # untouched when dbias is NULL
+    want = oracle_all(t)["dU"]
+    assert rel_err(to_f64(dev.dU), want) <= TOL["bf16"]
+
+
+# Full benchmark sizes, in the automatic plan the benchmark times.
+@pytest.mark.parametrize("w", [W.BERT_BASE_FFN_UP, W.BERT_BASE_PROJ[2], W.BERT_BASE_PROJ[4],
+                               W.BERT_LARGE_FFN_UP, W.BERT_LARGE_FFN_DOWN], ids=lambda w: w.name)
+def test_parity_full_size(sk, w):
+    check_all(sk, w, 0)
+
+
+def test_parity_llm_mlp_full_size_sampled(sk):
+    """Config 4 at full size: too large for a full oracle pass in seconds, so the
+    oracle evaluates 48 sampled token rows of y and dX, and 64 sampled output
+    columns of dU and db (each needs the whole token reduction)."""
+    w = W.LLM_MLP
+    print(f"case {w.name} full size (sampled)", flush=True)
+    sk.sk_set_plan(0)
+    t = W.generate(w)
+    dev = DeviceLayer(t, sk)
+    dev.run_all()
+    r = np.random.default_rng(123)
+    rows = np.sort(r.choice(w.tokens, 48, replace=False))
+    rows[0], rows[-1] = 0, w.tokens - 1
+    cols = np.sort(r.choice(w.d_out, 64, replace=False))
+    cols[0], cols[-1] = 0, w.d_out - 1
+    v = t.value
+    S, U = v["S"].astype(np.float64), v["U"].astype(np.float64)
+    y = O.forward(v["x"][rows].astype(np.float64), S, U, v["b"].astype(np.float64))
+    dX = O.grad_input(v["dY"][rows].astype(np.float64), S, U)
+    dYc = v["dY"][:, cols].astype(np.float64)
+    dU = O.grad_factors(v["x"].astype(np.float64), S, dYc).reshape(w.R, len(cols))
+    db = O.grad_bias(dYc)
+    rows_t = torch.from_numpy(rows).cuda()
+    cols_t = torch.from_numpy(cols).cuda()
+    errs = dict(
+        y=rel_err(to_f64(dev.y[rows_t]), y),
+        dX=rel_err(to_f64(dev.dX[rows_t]), dX),
+        dU=rel_err(to_f64(dev.dU[:, cols_t]), dU),
+        db=rel_err(to_f64(dev.db[cols_t]), db),
+    )
+    print("   errors:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= TOL["bf16"], (n, e)
+    assert torch.isfinite(dev.y.float()).all() and torch.isfinite(dev.dX.float()).all()
+    assert torch.isfinite(dev.dU).all() and torch.isfinite(dev.db).all()
+
+
+def test_bit_reproducible(sk):
+    """The token reduction of dU/db runs in a fixed order: two runs agree bit for bit."""
+    sk.sk_set_plan(0)
+    t = W.generate(W.scaled(W.BERT_BASE_FFN_UP, tokens=2000))
+    dev = DeviceLayer(t, sk)
+    dev.run_all()
+    first = [a.clone() for a in (dev.y, dev.dX, dev.dU, dev.db)]
+    for a in (dev.y, dev.dX, dev.dU, dev.db):
+        a.fill_(float("nan"))
+    dev.run_all()
+    for a, b in zip(first, (dev.y, dev.dX, dev.dU, dev.db)):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_runs_on_a_side_stream(sk):
+    sk.sk_set_plan(0)
+    t = W.generate(W.Workload("bf16_stream", 500, 256, 320, 2, 32, "bf16", seed=8))
+    dev = DeviceLayer(t, sk)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for st in (dev.fwd(s), dev.bwd_input(s), dev.bwd_weight(s)):
+        sk.check(st)
+    s.synchronize()
+    want = oracle_all(t)
+    got = dict(y=to_f64(dev.y), dX=to_f64(dev.dX), dU=to_f64(dev.dU), db=to_f64(dev.db))
+    for n in want:
+        assert rel_err(got[n], want[n]) <= TOL["bf16"], n
+
+
+def test_workspace_too_small_is_an_error_not_a_launch(sk):
+    t = W.generate(W.Workload("bf16_ws", 64, 64, 64, 1, 16, "bf16", seed=9))
+    dev = DeviceLayer(t, sk)
+    sk.sk_set_plan(2)
+    st = sk.sk_linear_fwd(dev.x, dev.S_cat, dev.U_cat, dev.b, dev.y, *dev.args, dev.ws, 8, None)
+    assert st == sk.SK_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.isnan(dev.y.float()).all()
