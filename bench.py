@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the SKLinear hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One step = forward + input gradient + factor/bias gradient (the three libsk
+entry points) over one batch of synthetic input that is already resident in
+HBM.  Prints ONE JSON line.  `value` is tokens per second of the whole step;
+TFLOP/s and the per-call times ride along.  The roofline object is for the
+dominant call of the step (the entry point that takes the most time), timed
+live with HIP events on the launch stream: K back-to-back launches between
+two events.  Buffers are rotated through enough copies to exceed the 256 MB
+Infinity Cache ("cold"); the same loop on one buffer set is reported as warm.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+MFMA_F32_PEAK_TFLOPS = 157.3
+INFINITY_CACHE_BYTES = 256 << 20
+
+
+def algorithmic(w, op):
+    """(flops, HBM bytes) one call must do: operands read once, results written
+    once; the R-wide intermediate, its recomputation across tiles and cache
+    re-reads are not counted."""
+    e = 2 if w.dtype == "bf16" else 4
+    T, i, o, R = w.tokens, w.d_in, w.d_out, w.R
+    flops = 2 * T * R * (i + o)
+    if op == "fwd":
+        b = e * (T * (i + o) + R * (i + o) + o)
+    elif op == "bwd_input":
+        b = e * (T * (i + o) + R * (i + o))
+    else:
+        b = e * (T * (i + o) + i * R) + 4 * (R * o + o)
+    return flops, b
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c1_bert_base_ffn_up")
+    ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 fused, 2 two-pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-context", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "run it with --gpus 1")
+
+    import torch
+    from paper_2601_15473_amd import libsk as sk
+    from paper_2601_15473_amd import workloads as W
+    from paper_2601_15473_amd.device import DeviceLayer
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    w = W.BY_NAME[args.workload]
+    sk.sk_set_plan(args.plan)
+    tensors = W.generate(w)
+
+    # Buffer sets: enough copies that a full rotation exceeds twice the Infinity Cache.
+    one = DeviceLayer(tensors, sk, poison=False)
+    per_set = sum(t.numel() * t.element_size() for t in
+                  (one.x, one.dY, one.y, one.dX, one.dU, one.db, one.ws, one.S_cat, one.U_cat))
+    n_sets = max(2, min(64, int(np.ceil(2 * INFINITY_CACHE_BYTES / per_set))))
+    sets = [one] + [DeviceLayer(tensors, sk, poison=False) for _ in range(n_sets - 1)]
+
+    stream = torch.cuda.Stream()
+    ops = ("fwd", "bwd_input", "bwd_weight")
+
+    def call(d, op):
+        st = getattr(d, op)(stream)
+        if st != sk.SK_OK:
+            raise sk.SkError(st)
+
+    def step(d):
+        for op in ops:
+            call(d, op)
+
+    def timed(fn, n):
+        """ms per iteration of fn(i), n iterations between two events on the launch stream."""
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for i in range(n):
+                fn(i)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            step(sets[i % n_sets])
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly K steps, cold (rotating buffer sets) ----
+    t0 = time.perf_counter()
+    ms_step = timed(lambda i: step(sets[i % n_sets]), args.steps)
+    wall = time.perf_counter() - t0
+    ms_step_warm = timed(lambda i: step(one), args.steps)
+
+    # ---- per-call times, same protocol ----
+    per_op = {}
+    for op in ops:
+        per_op[op] = {
+            "ms": timed(lambda i, op=op: call(sets[i % n_sets], op), args.steps),
+            "ms_warm": timed(lambda i, op=op: call(one, op), args.steps),
+        }
+    flops_step = bytes_step = 0
+    for op in ops:
+        f, b = algorithmic(w, op)
+        flops_step += f
+        bytes_step += b
+        per_op[op].update(tflops=f / per_op[op]["ms"] / 1e9, gbs=b / per_op[op]["ms"] / 1e6)
+
+    # which roofline binds: arithmetic intensity against the ridge point
+    peak_tf = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
+    t_mfma = flops_step / (peak_tf * 1e12)
+    t_hbm = bytes_step / (HBM_PEAK_GBS * 1e9)
+    bound = "mfma" if t_mfma > t_hbm else "hbm"
+    dom = max(ops, key=lambda o: per_op[o]["ms"])
+    f_dom, b_dom = algorithmic(w, dom)
+    if bound == "hbm":
+        achieved, peak, unit = b_dom / per_op[dom]["ms"] / 1e6, HBM_PEAK_GBS, "GB/s"
+    else:
+        achieved, peak, unit = f_dom / per_op[dom]["ms"] / 1e9, peak_tf, "TFLOP/s"
+    roofline = {
+        "bound": bound, "kernel": f"sk_linear_{dom}", "achieved": achieved, "peak": peak,
+        "unit": unit, "frac": achieved / peak, "traffic": None,
+        "step_frac": max(t_mfma, t_hbm) / (ms_step * 1e-3),
+        "algorithmic_bytes": b_dom, "algorithmic_flops": f_dom, "ms": per_op[dom]["ms"],
+    }
+
+    out = {
+        "metric": "SKLinear fwd+bwd tokens/s (TFLOP/s and roofline fraction alongside)",
+        "value": w.tokens / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "tokens": w.tokens, "in": w.d_in, "out": w.d_out,
+                   "l": w.l, "k": w.k, "plan": args.plan, "buffer_sets": n_sets,
+                   "cache": "cold (buffer sets rotate, total > 2x Infinity Cache)"},
+        "tflops": flops_step / (ms_step * 1e-3) / 1e12,
+        "ms_per_step_warm": ms_step_warm,
+        "wall_s_timed_region": wall,
+        "per_call": per_op,
+        "roofline": roofline,
+    }
+
+    if not args.no_dense_context:
+        # the dense layer the sketch replaces (hipBLASLt through torch.matmul): context only
+        dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        Wd = torch.randn(w.d_out, w.d_in, device="cuda", dtype=dt)
+        x, dY = one.x, one.dY
+
+        def dense(i):
+            torch.matmul(x, Wd.t())
+            torch.matmul(dY, Wd)
+            torch.matmul(dY.t(), x)
+        with torch.cuda.stream(stream):
+            for i in range(5):
+                dense(i)
+        ms_dense = timed(dense, max(10, args.steps // 4))
+        out["dense_context"] = {"ms_per_step": ms_dense, "kind": "torch.matmul (hipBLASLt) x3",
+                                "tflops": 6 * w.tokens * w.d_in * w.d_out / ms_dense / 1e9}
+
+    if not args.no_cpu_baseline:
+        from oracle import sklinear as O
+        v = {n: a.astype(np.float64) for n, a in tensors.value.items()}
+
+        def oracle_step():
+            O.forward(v["x"], v["S"], v["U"], v.get("b"))
+            O.grad_input(v["dY"], v["S"], v["U"])
+            O.grad_factors(v["x"], v["S"], v["dY"])
+            O.grad_bias(v["dY"])
+        oracle_step()
+        reps, t_begin = 0, time.perf_counter()
+        while True:
+            oracle_step()
+            reps += 1
+            el = time.perf_counter() - t_begin
+            if el >= args.cpu_seconds or (reps >= 3 and el >= 0.5 * args.cpu_seconds):
+                break
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        out["cpu_baseline"] = {
+            "value": w.tokens * reps / el, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{reps} full passes of {w.name} (fwd + both gradients, fp64 numpy/OpenBLAS)",
+        }
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
