@@ -115,9 +115,13 @@ const char* sk_last_hip_error(void);
  * Tuning/testing knob, process-wide (not part of the layer's definition):
  * which kernel plan the three entry points pick.
  *   0 = automatic (default): per-shape choice;
- *   1 = force the fused plan (intermediate kept on chip) where the shape
- *       allows it, i.e. bf16 with R <= 512;
- *   2 = force the two-pass plan (intermediate through the workspace).
+ *   1 = fused: one kernel per call, the R-wide intermediate of a token tile never
+ *       leaves the chip (bf16 with R <= 256; wider R falls back to plan 3, then 2);
+ *   2 = two general GEMMs with the intermediate in the workspace (any dtype);
+ *   3 = split-K first contraction into fp32 slabs in the workspace, then a second
+ *       kernel that sums the slabs into LDS and keeps the tile on chip (bf16, R <= 512;
+ *       otherwise plan 2).
+ * Only sk_linear_fwd and sk_linear_bwd_input have several plans.
  * sk_linear_workspace_bytes reports the maximum over the plans, so a workspace
  * sized by it serves whatever is selected.  Returns the previous value, or -1
  * (and changes nothing) for a value out of range.

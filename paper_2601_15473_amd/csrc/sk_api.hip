@@ -103,19 +103,81 @@ WeightPlan plan_weight(const Shape& s) {
   return w;
 }
 
-bool use_chain(const Shape& s) {
-  const int plan = g_plan.load(std::memory_order_relaxed);
-  if (s.dtype != SK_BF16 || !chain_supported(s.R) || plan == 2) return false;
-  if (plan == 1) return true;
-  return false;  // automatic choice: two-pass until the fused plan is measured faster
+// Kernel plans of the forward and the input gradient.
+enum Plan : int {
+  PLAN_AUTO = 0,
+  PLAN_FUSED = 1,         // one kernel, intermediate tile never leaves the chip (bf16, R <= 256)
+  PLAN_TWO_GEMM = 2,      // two general GEMMs, bf16/fp32 intermediate through the workspace
+  PLAN_SPLIT_EXPAND = 3,  // split-K sketch GEMM into fp32 slabs, then the expand kernel that
+                          // sums them on the way into LDS (bf16, R <= 512)
+};
+
+Plan pick_plan(const Shape& s) {
+  const int forced = g_plan.load(std::memory_order_relaxed);
+  const bool chain_ok = s.dtype == SK_BF16 && chain_supported(s.R);
+  const bool fused_ok = chain_ok && s.R <= CHAIN_FUSED_MAX_R;
+  switch (forced) {
+    case PLAN_FUSED: return fused_ok ? PLAN_FUSED : (chain_ok ? PLAN_SPLIT_EXPAND : PLAN_TWO_GEMM);
+    case PLAN_TWO_GEMM: return PLAN_TWO_GEMM;
+    case PLAN_SPLIT_EXPAND: return chain_ok ? PLAN_SPLIT_EXPAND : PLAN_TWO_GEMM;
+    default: break;
+  }
+  // automatic: the on-chip plans pay off while the layer is bandwidth bound
+  if (chain_ok && s.R <= 256) return PLAN_SPLIT_EXPAND;
+  return PLAN_TWO_GEMM;
+}
+
+// Split of the first contraction (M = tokens, N = R, contraction length K) so that a
+// skinny output still fills the chip: fp32 slabs, one per k range, summed in order by
+// the consumer.  splits == 1 means the bf16 result is written directly.
+struct SketchPlan {
+  int tile, splits, k_per_split;
+  size_t bytes;
+};
+
+SketchPlan plan_sketch(const Shape& s, int64_t K) {
+  SketchPlan q{};
+  q.tile = s.R <= 64 ? TILE_64x64 : (s.R <= 256 ? TILE_64x128 : TILE_128x128);
+  int bm, bn;
+  tile_dims(q.tile, bm, bn);
+  const int64_t tiles = ((s.T + bm - 1) / bm) * ((s.R + bn - 1) / bn);
+  int64_t splits = (NUM_CUS + tiles - 1) / tiles;
+  const int64_t max_splits = K / 128 > 0 ? K / 128 : 1;   // at least two k chunks each
+  if (splits > max_splits) splits = max_splits;
+  if (splits > 8) splits = 8;
+  if (splits < 1) splits = 1;
+  int64_t kps = (K + splits - 1) / splits;
+  kps = (kps + 63) / 64 * 64;
+  splits = (K + kps - 1) / kps;
+  q.splits = (int)splits;
+  q.k_per_split = (int)kps;
+  q.bytes = splits > 1 ? align_up((size_t)splits * s.T * s.R * 4) : align_up((size_t)s.T * s.R * 2);
+  return q;
+}
+
+// Number of N slices of the expand/fused kernel: about two work-groups per CU.
+int chain_slices(int64_t T, int64_t N) {
+  const int64_t tiles_m = (T + 63) / 64;
+  const int64_t n_tiles = (N + chain_bn() - 1) / chain_bn();
+  int64_t sl = (2 * NUM_CUS + tiles_m - 1) / tiles_m;
+  if (sl > n_tiles) sl = n_tiles;
+  if (sl < 1) sl = 1;
+  return (int)sl;
 }
 
 size_t workspace_for(sk_op op, const Shape& s) {
   const size_t mid = align_up((size_t)s.T * s.R * s.esize);  // Z or G
   switch (op) {
     case SK_OP_FWD:
-    case SK_OP_BWD_INPUT:
-      return mid;  // the fused plan needs none; report the maximum over plans
+    case SK_OP_BWD_INPUT: {
+      // the maximum over the plans, so one buffer serves whichever is selected
+      size_t need = mid;
+      if (s.dtype == SK_BF16 && chain_supported(s.R)) {
+        const size_t b = plan_sketch(s, op == SK_OP_FWD ? s.in : s.out).bytes;
+        if (b > need) need = b;
+      }
+      return need;
+    }
     case SK_OP_BWD_WEIGHT:
       return plan_weight(s).total();
   }
@@ -158,7 +220,7 @@ const char* sk_status_string(sk_status status) {
 const char* sk_last_hip_error(void) { return g_hip_error.c_str(); }
 
 int sk_set_plan(int plan) {
-  if (plan < 0 || plan > 2) return -1;
+  if (plan < 0 || plan > 3) return -1;
   return g_plan.exchange(plan);
 }
 
@@ -184,16 +246,26 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
   const float scale = 1.0f / (float)l;
   g_hip_error.clear();
 
-  if (use_chain(s)) {
+  const Plan plan = pick_plan(s);
+  if (plan != PLAN_FUSED && (!workspace || workspace_bytes < workspace_for(SK_OP_FWD, s)))
+    return SK_ERR_WORKSPACE;
+  if (plan == PLAN_FUSED || plan == PLAN_SPLIT_EXPAND) {
     ChainArgs c{};
     c.A = x; c.B1 = S_cat; c.B2 = U_cat; c.bias = bias; c.C = y;
     c.lda = in; c.ldb1 = s.R; c.ldb2 = out; c.ldc = out;
     c.M = (int)tokens; c.K1 = (int)in; c.R = s.R; c.N = (int)out; c.scale = scale;
-    const hipError_t e = launch_chain_bf16(false, c, hs);
-    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_fwd (fused)");
+    c.n_slices = chain_slices(tokens, out);
+    if (plan == PLAN_SPLIT_EXPAND) {
+      const SketchPlan q = plan_sketch(s, in);
+      GemmArgs a = dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr);
+      a.splits = q.splits; a.k_per_split = q.k_per_split;
+      const hipError_t e1 = launch_gemm_bf16(q.splits > 1 ? GEMM_NN_F32 : GEMM_NN, q.tile, a, hs);
+      if (e1 != hipSuccess) return hip_fail(e1, "sk_linear_fwd (x.S, split)");
+      c.Z = workspace; c.z_splits = q.splits > 1 ? q.splits : 0; c.z_slab = (int64_t)tokens * s.R;
+    }
+    const hipError_t e = launch_chain_bf16(false, plan == PLAN_FUSED, c, hs);
+    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_fwd (expand)");
   }
-  const size_t need = align_up((size_t)s.T * s.R * s.esize);
-  if (!workspace || workspace_bytes < need) return SK_ERR_WORKSPACE;
   // Z = x . S_cat, then y = scale * Z . U_cat + bias
   hipError_t e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (x.S)");
@@ -217,16 +289,26 @@ sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_c
   const float scale = 1.0f / (float)l;
   g_hip_error.clear();
 
-  if (use_chain(s)) {
+  const Plan plan = pick_plan(s);
+  if (plan != PLAN_FUSED && (!workspace || workspace_bytes < workspace_for(SK_OP_BWD_INPUT, s)))
+    return SK_ERR_WORKSPACE;
+  if (plan == PLAN_FUSED || plan == PLAN_SPLIT_EXPAND) {
     ChainArgs c{};
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-    const hipError_t e = launch_chain_bf16(true, c, hs);
-    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd_input (fused)");
+    c.n_slices = chain_slices(tokens, in);
+    if (plan == PLAN_SPLIT_EXPAND) {
+      const SketchPlan q = plan_sketch(s, out);
+      GemmArgs a = dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr);
+      a.splits = q.splits; a.k_per_split = q.k_per_split;
+      const hipError_t e1 = launch_gemm_bf16(q.splits > 1 ? GEMM_NT_F32 : GEMM_NT, q.tile, a, hs);
+      if (e1 != hipSuccess) return hip_fail(e1, "sk_linear_bwd_input (dY.U^T, split)");
+      c.Z = workspace; c.z_splits = q.splits > 1 ? q.splits : 0; c.z_slab = (int64_t)tokens * s.R;
+    }
+    const hipError_t e = launch_chain_bf16(true, plan == PLAN_FUSED, c, hs);
+    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd_input (expand)");
   }
-  const size_t need = align_up((size_t)s.T * s.R * s.esize);
-  if (!workspace || workspace_bytes < need) return SK_ERR_WORKSPACE;
   // G = dY . U_cat^T (U_cat read as [N = R, K = out]), then dX = scale * G . S_cat^T
   hipError_t e = gemm(s, GEMM_NT, dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_input (dY.U^T)");

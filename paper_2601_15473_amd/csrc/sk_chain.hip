@@ -1,10 +1,287 @@
-// Fused two-stage chain (intermediate kept in LDS) -- bf16, R <= 512.
+// The "expand" half of SKLinear for small sketch widths (bf16, R <= 512), with the
+// R-wide intermediate resident on chip, and optionally the "sketch" half fused in
+// front of it:
+//
+//   C[M, N] = scale * Zt . B2 (+ bias),   Zt = the bf16 R-wide intermediate of a
+//   64-token tile, either
+//     - computed here:  Zt = bf16(A[64 tokens, K1] . B1)            (FUSED), or
+//     - read from the workspace: bf16 [M, R], or the sum of fp32 split-K slabs.
+//
+// A work-group (256 threads, 4 waves) owns one 64-token tile and one slice of the N
+// range.  Zt sits in LDS once and every wave lifts the whole of it into registers
+// as MFMA fragments; the waves then split each BN-wide tile of N four ways, so a B2
+// fragment is read from LDS by exactly one wave and used for both 32-row blocks.
+// B2 streams through a double-buffered LDS chunk (64 of the R rows at a time)
+// across tile boundaries, so the load of the next tile overlaps the MFMAs and the
+// stores of the current one.  Output tiles leave through an LDS re-layout as whole
+// 2*BN-byte rows.
+#include "sk_bf16_tile.h"
 #include "sk_launch.h"
 
 namespace sk {
 
-bool chain_supported(int) { return false; }
-int chain_bm(int) { return 0; }
-hipError_t launch_chain_bf16(bool, const ChainArgs&, hipStream_t) { return hipErrorNotSupported; }
+constexpr int CH_BM = 64;
+
+template <int RT, int BN, bool B2_KC, bool FUSED, bool B1_KC>
+struct ChainLds {
+  typedef OpTile<BN, B2_KC> TB2;
+  typedef OpTile<CH_BM, true> TA;
+  typedef OpTile<RT, B1_KC> TB1;
+  static constexpr int Z_LD = RT + 8;
+  static constexpr int Z_BYTES = CH_BM * Z_LD * 2;
+  static constexpr int OUT_LD = BN * 2 + 8;                       // bytes per staged output row
+  static constexpr int S2_BYTES = 2 * TB2::ELEMS * 2 + CH_BM * OUT_LD;
+  static constexpr int S1_BYTES = FUSED ? 2 * (TA::ELEMS + TB1::ELEMS) * 2 : 0;
+  static constexpr int BYTES = Z_BYTES + (S1_BYTES > S2_BYTES ? S1_BYTES : S2_BYTES);
+};
+
+template <int RT, int BN, bool B2_KC, bool FUSED, bool B1_KC>
+__global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
+  typedef ChainLds<RT, BN, B2_KC, FUSED, B1_KC> L;
+  typedef typename L::TB2 TB2;
+  constexpr int KC = RT / 64;            // k chunks of stage 2
+  constexpr int WN = BN / 4, TN = WN / 32;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[L::BYTES];
+  bf16* const Zs = reinterpret_cast<bf16*>(smem);
+  unsigned char* const work = smem + L::Z_BYTES;
+  bf16* const Bbuf = reinterpret_cast<bf16*>(work);
+  unsigned char* const ostage = work + 2 * TB2::ELEMS * 2;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile_m = blockIdx.x / p.n_slices, slice = blockIdx.x % p.n_slices;
+  const int m0 = tile_m * CH_BM;
+
+  // this work-group's run of BN-wide tiles
+  const int n_tiles = (p.N + BN - 1) / BN;
+  const int per_slice = (n_tiles + p.n_slices - 1) / p.n_slices;
+  const int t_begin = slice * per_slice;
+  const int t_end = (t_begin + per_slice < n_tiles) ? t_begin + per_slice : n_tiles;
+  const int my_tiles = t_end - t_begin;
+  if (my_tiles <= 0) return;  // uniform over the work-group
+
+  const bf16* __restrict__ B2 = static_cast<const bf16*>(p.B2);
+  uint4 rb[TB2::PIECES];
+  // first B2 chunk goes in flight before anything else
+  TB2::load(rb, B2, p.ldb2, t_begin * BN, p.N, 0, p.R, tid);
+
+  // ---------------- the intermediate tile Zt -> LDS ----------------
+  if (FUSED) {
+    typedef typename L::TA TA;
+    typedef typename L::TB1 TB1;
+    constexpr int STAGE = TA::ELEMS + TB1::ELEMS;
+    constexpr int TN1 = RT / 64;  // waves 2 x 2: each 32 rows x RT/2 columns
+    bf16* const s1 = reinterpret_cast<bf16*>(work);
+    const bf16* __restrict__ A = static_cast<const bf16*>(p.A);
+    const bf16* __restrict__ B1 = static_cast<const bf16*>(p.B1);
+    const int wm = wave >> 1, wn = wave & 1;
+    f32x16 acc1[TN1];
+#pragma unroll
+    for (int j = 0; j < TN1; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc1[j][r] = 0.f;
+    uint4 ra[TA::PIECES], rb1[TB1::PIECES];
+    const int nk = (p.K1 + BK - 1) / BK;
+    TA::load(ra, A, p.lda, m0, p.M, 0, p.K1, tid);
+    TB1::load(rb1, B1, p.ldb1, 0, p.R, 0, p.K1, tid);
+    TA::store(s1, ra, tid);
+    TB1::store(s1 + TA::ELEMS, rb1, tid);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+      const bf16* As = s1 + (kc & 1) * STAGE;
+      const bf16* Bs = As + TA::ELEMS;
+      const bool more = kc + 1 < nk;
+      if (more) {
+        TA::load(ra, A, p.lda, m0, p.M, (kc + 1) * BK, p.K1, tid);
+        TB1::load(rb1, B1, p.ldb1, 0, p.R, (kc + 1) * BK, p.K1, tid);
+      }
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        const bf16x8 fa = read_frag<true, TA::LD>(As, wm * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < TN1; ++j) {
+          const bf16x8 fb = read_frag<B1_KC, TB1::LD>(Bs, wn * (RT / 2) + j * 32, ks, lane);
+          acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc1[j], 0, 0, 0);
+        }
+      }
+      if (more) {
+        bf16* An = s1 + ((kc + 1) & 1) * STAGE;
+        TA::store(An, ra, tid);
+        TB1::store(An + TA::ELEMS, rb1, tid);
+      }
+      __syncthreads();
+    }
+    // round once to bf16: lane owns row l % 32 and 4 consecutive columns per q
+#pragma unroll
+    for (int j = 0; j < TN1; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = wn * (RT / 2) + j * 32 + q * 8 + (lane >> 5) * 4;
+        uint2 w;
+        w.x = pack_bf16x2(acc1[j][q * 4 + 0], acc1[j][q * 4 + 1]);
+        w.y = pack_bf16x2(acc1[j][q * 4 + 2], acc1[j][q * 4 + 3]);
+        *reinterpret_cast<uint2*>(Zs + (wm * 32 + (lane & 31)) * L::Z_LD + c) = w;
+      }
+  } else if (p.z_splits == 0) {
+    // bf16 [M, R] from the workspace; columns >= R and rows >= M read as zero
+    const bf16* __restrict__ Z = static_cast<const bf16*>(p.Z);
+    constexpr int PPR = RT / 8;
+#pragma unroll
+    for (int i = 0; i < (CH_BM * PPR) / 256; ++i) {
+      const int piece = i * 256 + tid;
+      const int r = piece / PPR, c = (piece % PPR) * 8;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (m0 + r < p.M && c < p.R) v = *reinterpret_cast<const uint4*>(Z + (int64_t)(m0 + r) * p.R + c);
+      *reinterpret_cast<uint4*>(Zs + r * L::Z_LD + c) = v;
+    }
+  } else {
+    // sum of fp32 split-K slabs, slabs added in index order, rounded once to bf16
+    const float* __restrict__ Zp = static_cast<const float*>(p.Z);
+    constexpr int PPR = RT / 4;
+#pragma unroll 2
+    for (int i = 0; i < (CH_BM * PPR) / 256; ++i) {
+      const int piece = i * 256 + tid;
+      const int r = piece / PPR, c = (piece % PPR) * 4;
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (m0 + r < p.M && c < p.R) {
+        const float* src = Zp + (int64_t)(m0 + r) * p.R + c;
+        s = *reinterpret_cast<const float4*>(src);
+        for (int k = 1; k < p.z_splits; ++k) {
+          const float4 v = *reinterpret_cast<const float4*>(src + (int64_t)k * p.z_slab);
+          s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+      }
+      uint2 w;
+      w.x = pack_bf16x2(s.x, s.y);
+      w.y = pack_bf16x2(s.z, s.w);
+      *reinterpret_cast<uint2*>(Zs + r * L::Z_LD + c) = w;
+    }
+  }
+  __syncthreads();  // Zt complete; stage-1 buffers (aliasing Bbuf) are free
+
+  // every wave lifts all of Zt into registers, in MFMA fragment layout
+  bf16x8 fa[2][RT / 16];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int ks = 0; ks < RT / 16; ++ks)
+      fa[i][ks] = read_frag<true, L::Z_LD>(Zs, i * 32, ks, lane);
+
+  TB2::store(Bbuf, rb, tid);
+  __syncthreads();
+
+  // ---------------- stage 2: stream B2, one BN-wide output tile at a time ----------------
+  f32x16 acc[2][TN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  bf16* __restrict__ C = static_cast<bf16*>(p.C);
+  const bf16* __restrict__ bias = static_cast<const bf16*>(p.bias);
+  const float scale = p.scale;
+  const int n_it = my_tiles * KC;
+  int it = 0;
+  for (int jt = 0; jt < my_tiles; ++jt) {
+    const int n0 = (t_begin + jt) * BN;
+#pragma unroll
+    for (int c = 0; c < KC; ++c, ++it) {
+      const bf16* Bs = Bbuf + (it & 1) * TB2::ELEMS;
+      const bool more = it + 1 < n_it;
+      if (more) {
+        const int nn0 = (c + 1 < KC) ? n0 : n0 + BN;
+        const int k0 = (c + 1 < KC) ? (c + 1) * 64 : 0;
+        TB2::load(rb, B2, p.ldb2, nn0, p.N, k0, p.R, tid);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const bf16x8 fb = read_frag<B2_KC, TB2::LD>(Bs, wave * WN + j * 32, ks, lane);
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[i][c * 4 + ks], acc[i][j], 0, 0, 0);
+        }
+      }
+      if (c == KC - 1) {
+        // tile finished: scale, bias, round, re-lay out through LDS, store whole rows
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int cc = wave * WN + j * 32 + q * 8 + (lane >> 5) * 4;  // column in the tile
+              float v[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                v[e] = acc[i][j][q * 4 + e] * scale;
+                acc[i][j][q * 4 + e] = 0.f;
+              }
+              if (bias != nullptr && n0 + cc < p.N) {
+                const uint2 bb = *reinterpret_cast<const uint2*>(bias + n0 + cc);
+                v[0] += bf16_bits_to_float(bb.x & 0xffffu);
+                v[1] += bf16_bits_to_float(bb.x >> 16);
+                v[2] += bf16_bits_to_float(bb.y & 0xffffu);
+                v[3] += bf16_bits_to_float(bb.y >> 16);
+              }
+              uint2 w;
+              w.x = pack_bf16x2(v[0], v[1]);
+              w.y = pack_bf16x2(v[2], v[3]);
+              *reinterpret_cast<uint2*>(ostage + (i * 32 + (lane & 31)) * L::OUT_LD + cc * 2) = w;
+            }
+        __syncthreads();
+        constexpr int PPR = BN / 4;  // 8-byte pieces per output row
+#pragma unroll
+        for (int s = 0; s < (CH_BM * PPR) / 256; ++s) {
+          const int idx = s * 256 + tid;
+          const int r = idx / PPR, pc = idx % PPR;
+          const int gm = m0 + r, gn = n0 + pc * 4;
+          if (gm < p.M && gn < p.N)
+            *reinterpret_cast<uint2*>(C + (int64_t)gm * p.ldc + gn) =
+                *reinterpret_cast<const uint2*>(ostage + r * L::OUT_LD + pc * 8);
+        }
+      }
+      if (more) TB2::store(Bbuf + ((it + 1) & 1) * TB2::ELEMS, rb, tid);
+      __syncthreads();
+    }
+  }
+}
+
+bool chain_supported(int R) { return R >= 16 && R <= 512; }
+
+template <int RT, int BN, bool B2_KC, bool FUSED, bool B1_KC>
+static hipError_t launch_one(const ChainArgs& a, hipStream_t s) {
+  const long long grid = (long long)a.tiles_m * a.n_slices;
+  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((chain_kernel<RT, BN, B2_KC, FUSED, B1_KC>), dim3((unsigned)grid), dim3(256), 0,
+                     s, a);
+  return hipGetLastError();
+}
+
+template <bool B_KC, bool FUSED>
+static hipError_t launch_rt(const ChainArgs& a, hipStream_t s) {
+  constexpr int BN = 128;
+  if (a.R <= 64) return launch_one<64, BN, B_KC, FUSED, B_KC>(a, s);
+  if (a.R <= 128) return launch_one<128, BN, B_KC, FUSED, B_KC>(a, s);
+  if (a.R <= 192) return launch_one<192, BN, B_KC, FUSED, B_KC>(a, s);
+  if (a.R <= 256) return launch_one<256, BN, B_KC, FUSED, B_KC>(a, s);
+  if (!FUSED) {  // the fused form needs LDS for both stages: R <= 256 only
+    if (a.R <= 384) return launch_one<384, BN, B_KC, false, B_KC>(a, s);
+    if (a.R <= 512) return launch_one<512, BN, B_KC, false, B_KC>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+int chain_bn() { return 128; }
+
+hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s) {
+  if (!chain_supported(a.R) || a.n_slices < 1 || (fused && a.R > CHAIN_FUSED_MAX_R))
+    return hipErrorInvalidValue;
+  a.tiles_m = (a.M + CH_BM - 1) / CH_BM;
+  if (b_kc) return fused ? launch_rt<true, true>(a, s) : launch_rt<true, false>(a, s);
+  return fused ? launch_rt<false, true>(a, s) : launch_rt<false, false>(a, s);
+}
 
 }  // namespace sk

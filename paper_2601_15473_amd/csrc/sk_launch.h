@@ -8,6 +8,8 @@ enum GemmKind : int {
   GEMM_NN = 0,      // A [M,K], B [K,N]            -> storage type
   GEMM_NT = 1,      // A [M,K], B [N,K]            -> storage type
   GEMM_TN_F32 = 2,  // A [K,M], B [K,N], split-K   -> fp32 (+ column sums of B)
+  GEMM_NN_F32 = 3,  // as GEMM_NN, split-K          -> fp32 slabs
+  GEMM_NT_F32 = 4,  // as GEMM_NT, split-K          -> fp32 slabs
 };
 
 enum TileCfg : int {
@@ -33,24 +35,31 @@ constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16;
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s);
 
-// Fused two-stage chain for bf16 with the R-wide intermediate kept in LDS:
-//   C[M, N] = scale * ((A . B1) rounded to bf16) . B2 (+ bias),  R <= 512.
+// Second contraction of the layer with the R-wide intermediate of a 64-token tile
+// resident on chip (bf16, R <= 512), optionally with the first contraction fused in:
+//   C[M, N] = scale * Zt . B2 (+ bias)
+//   fused    : Zt = bf16(A[M, K1] . B1)                       (R <= 256)
+//   not fused: Zt read from Z: bf16 [M, R] when z_splits == 0, else the sum of
+//              z_splits fp32 slabs [M, R] that are z_slab elements apart
 //   b_kc = false: B1 [K1, R], B2 [R, N]   (forward:      x, S_cat, U_cat)
 //   b_kc = true : B1 [R, K1], B2 [N, R]   (input grad:   dY, U_cat, S_cat)
 struct ChainArgs {
-  const void* A;       // [M, K1]
-  const void* B1;
+  const void* A;       // [M, K1]      (fused)
+  const void* B1;      //              (fused)
+  const void* Z;       //              (not fused)
   const void* B2;
   const void* bias;    // [N] or null
   void* C;             // [M, N]
-  int64_t lda, ldb1, ldb2, ldc;
+  int64_t lda, ldb1, ldb2, ldc, z_slab;
   int M, K1, R, N;
-  int n_slices;        // the N range is cut into this many slices, one per work-group column
-  int tiles_m;
+  int z_splits;
+  int n_slices;        // the N range is cut into this many runs of tiles, one per work-group
+  int tiles_m;         // filled in by the launcher
   float scale;
 };
 bool chain_supported(int R);
-int chain_bm(int R);
-hipError_t launch_chain_bf16(bool b_kc, const ChainArgs& a, hipStream_t s);
+constexpr int CHAIN_FUSED_MAX_R = 256;
+int chain_bn();
+hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s);
 
 }  // namespace sk

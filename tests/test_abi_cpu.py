@@ -65,7 +65,8 @@ def test_workspace_query_and_check():
             a = (1000, 768, 3072, 2, 64, dt)
             mid = 1000 * 128 * e
             for op in (sk.SK_OP_FWD, sk.SK_OP_BWD_INPUT):
-                assert mid <= sk.sk_linear_workspace_bytes(op, *a) < mid + 256
+                ws = sk.sk_linear_workspace_bytes(op, *a)
+                assert ws >= mid and ws % 256 == 0 and ws <= 8 * 4 * 1000 * 128 + 256
             assert sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT, *a) >= mid
         need = sk.sk_linear_workspace_bytes(sk.SK_OP_FWD, *ARGS)
         assert sk.sk_linear_fwd(P, P, P, P, P, *ARGS, P, need - 1) == sk.SK_ERR_WORKSPACE
@@ -78,7 +79,7 @@ def test_workspace_query_and_check():
 
 
 def test_set_plan():
-    assert sk.sk_set_plan(5) == -1
+    assert sk.sk_set_plan(4) == -1 and sk.sk_set_plan(-1) == -1
     prev = sk.sk_set_plan(2)
     assert sk.sk_set_plan(prev) == 2
 

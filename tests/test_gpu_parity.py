@@ -65,12 +65,12 @@ SMALL = [
 
 
 @pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
-@pytest.mark.parametrize("plan", [2, 1], ids=["two_pass", "fused"])
+@pytest.mark.parametrize("plan", [2, 1, 3], ids=["two_gemm", "fused", "split_expand"])
 def test_parity_small(sk, w, plan):
     check_all(sk, w, plan)
 
 
-@pytest.mark.parametrize("plan", [2, 1], ids=["two_pass", "fused"])
+@pytest.mark.parametrize("plan", [2, 1, 3], ids=["two_gemm", "fused", "split_expand"])
 def test_no_bias_and_no_dbias(sk, plan):
     w = W.Workload("bf16_nobias", 150, 128, 96, 2, 32, "bf16", seed=6)
     check_all(sk, w, plan, with_bias=False)
