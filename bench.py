@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-context", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -67,6 +68,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     w = W.BY_NAME[args.workload]
+    if args.tokens:
+        w = W.scaled(w, tokens=args.tokens)
     sk.sk_set_plan(args.plan)
     tensors = W.generate(w)
 

@@ -1,6 +1,7 @@
 // libsk's C ABI (include/sk.h): argument validation, per-shape plan, launches.
 // Validation runs before any HIP call, so error paths work without a GPU.
 #include <atomic>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 
@@ -156,10 +157,11 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
 }
 
 // Number of N slices of the expand/fused kernel: about two work-groups per CU.
-int chain_slices(int64_t T, int64_t N) {
+int chain_slices(int64_t T, int64_t N, int R) {
   const int64_t tiles_m = (T + 63) / 64;
-  const int64_t n_tiles = (N + chain_bn() - 1) / chain_bn();
+  const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
   int64_t sl = (2 * NUM_CUS + tiles_m - 1) / tiles_m;
+  if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
   return (int)sl;
@@ -254,7 +256,7 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
     c.A = x; c.B1 = S_cat; c.B2 = U_cat; c.bias = bias; c.C = y;
     c.lda = in; c.ldb1 = s.R; c.ldb2 = out; c.ldc = out;
     c.M = (int)tokens; c.K1 = (int)in; c.R = s.R; c.N = (int)out; c.scale = scale;
-    c.n_slices = chain_slices(tokens, out);
+    c.n_slices = chain_slices(tokens, out, s.R);
     if (plan == PLAN_SPLIT_EXPAND) {
       const SketchPlan q = plan_sketch(s, in);
       GemmArgs a = dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr);
@@ -297,7 +299,7 @@ sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_c
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-    c.n_slices = chain_slices(tokens, in);
+    c.n_slices = chain_slices(tokens, in, s.R);
     if (plan == PLAN_SPLIT_EXPAND) {
       const SketchPlan q = plan_sketch(s, out);
       GemmArgs a = dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr);

@@ -14,11 +14,29 @@
 
 namespace sk {
 
+// One scheduling phase: NM MFMAs with ND LDS reads, NV global loads and NW LDS stores
+// spread evenly between them, then a fence for the scheduler.
+template <int NM, int ND, int NV, int NW, int I = 0>
+__device__ __forceinline__ void sched_phase() {
+  if constexpr (I < NM) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    constexpr int d = (I + 1) * ND / NM - I * ND / NM;
+    constexpr int v = (I + 1) * NV / NM - I * NV / NM;
+    constexpr int w = (I + 1) * NW / NM - I * NW / NM;
+    if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x100, d, 0);
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+    if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+    sched_phase<NM, ND, NV, NW, I + 1>();
+  } else {
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <typename OutT> struct OutTraits;
 template <> struct OutTraits<bf16> { static constexpr int PIECE = 8; };    // 4 bf16
 template <> struct OutTraits<float> { static constexpr int PIECE = 16; };  // 4 fp32
 
-template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
+template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM, int PF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
   typedef OpTile<BM, A_KC> TA;
   typedef OpTile<BN, B_KC> TB;
@@ -67,50 +85,116 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) ones[j] = (bf16)1.0f;
 
-  uint4 ra[TA::PIECES], rb[TB::PIECES];
-  if (nk > 0) {
-    TA::load(ra, A, p.lda, m0, p.M, k_begin, k_end, tid);
-    TB::load(rb, B, p.ldb, n0, p.N, k_begin, k_end, tid);
-    TA::store(lds, ra, tid);
-    TB::store(lds + TA::ELEMS, rb, tid);
-  }
-  __syncthreads();
-
-  for (int kc = 0; kc < nk; ++kc) {
-    const bf16* As = lds + (kc & 1) * STAGE;
+  // One k step (16 wide): fragments of the four steps of a chunk are read one step
+  // ahead of the MFMAs that use them (two fragment sets), so LDS latency hides
+  // behind the matrix pipe.
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  auto read = [&](const bf16* As, int ks, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
     const bf16* Bs = As + TA::ELEMS;
-    const bool more = kc + 1 < nk;
-    if (more) {
-      const int k0 = k_begin + (kc + 1) * BK;
-      TA::load(ra, A, p.lda, m0, p.M, k0, k_end, tid);
-      TB::load(rb, B, p.ldb, n0, p.N, k0, k_end, tid);
-    }
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+    for (int i = 0; i < TM; ++i) fa[i] = read_frag<A_KC, TA::LD>(As, wm * WM + i * 32, ks, lane);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = read_frag<A_KC, TA::LD>(As, wm * WM + i * 32, ks, lane);
+    for (int j = 0; j < TN; ++j) fb[j] = read_frag<B_KC, TB::LD>(Bs, wn * WN + j * 32, ks, lane);
+  };
+  auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = read_frag<B_KC, TB::LD>(Bs, wn * WN + j * 32, ks, lane);
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    if (COLSUM) {
+      if (do_colsum) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-      if (COLSUM) {
-        if (do_colsum) {
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            csum[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], ones, csum[j], 0, 0, 0);
-        }
+          csum[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], ones, csum[j], 0, 0, 0);
       }
     }
-    if (more) {
+  };
+  // Work per chunk and thread: NMMA MFMAs per k step, NDSR fragment reads per k step,
+  // NVM global loads and as many LDS stores per chunk.  Each k step is one scheduling
+  // phase in which the other instructions are spread evenly between the MFMAs
+  // (sched_phase), so they issue in the shadow of the matrix pipe instead of in a
+  // burst that stalls it (the texture path takes 16 cycles per 16-byte-per-lane load).
+  constexpr int NDSR = (A_KC ? TM : 2 * TM) + (B_KC ? TN : 2 * TN);
+  constexpr int NMMA = TM * TN;
+  constexpr int NVM = TA::PIECES + TB::PIECES;
+
+  // Iteration shape (PF == 1): the global loads of chunk kc + 1 are issued during k
+  // steps 0 and 1 of chunk kc and stored to the other LDS buffer during k step 3.
+  // Chunks past the end of the k range load as zeros: no branch around any load.
+  if (PF == 1) {
+    uint4 ra[TA::PIECES], rb[TB::PIECES];
+    TA::load(ra, A, p.lda, m0, p.M, k_begin, k_end, p.K, tid);
+    TB::load(rb, B, p.ldb, n0, p.N, k_begin, k_end, p.K, tid);
+    TA::store(lds, ra, tid);
+    TB::store(lds + TA::ELEMS, rb, tid);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+      const bf16* As = lds + (kc & 1) * STAGE;
       bf16* An = lds + ((kc + 1) & 1) * STAGE;
+      const int k0 = k_begin + (kc + 1) * BK;
+      read(As, 0, fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      // k step 0: MFMAs + fragment reads of step 1 + the A loads of the next chunk
+      read(As, 1, fa1, fb1);
+      TA::load(ra, A, p.lda, m0, p.M, k0, k_end, p.K, tid);
+      mma(fa0, fb0);
+      sched_phase<NMMA, NDSR, TA::PIECES, 0>();
+      // k step 1: + the B loads of the next chunk
+      read(As, 2, fa0, fb0);
+      TB::load(rb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
+      mma(fa1, fb1);
+      sched_phase<NMMA, NDSR, TB::PIECES, 0>();
+      // k step 2
+      read(As, 3, fa1, fb1);
+      mma(fa0, fb0);
+      sched_phase<NMMA, NDSR, 0, 0>();
+      // k step 3: MFMAs + LDS stores of the next chunk
+      mma(fa1, fb1);
       TA::store(An, ra, tid);
       TB::store(An + TA::ELEMS, rb, tid);
+      sched_phase<NMMA, 0, 0, NVM>();
+      __syncthreads();
     }
+  } else {
+    // Small tiles: an iteration is too short to cover a load's latency, so two
+    // register sets keep the loads of chunk kc + 2 in flight while chunk kc + 1,
+    // loaded one iteration earlier, is stored.
+    uint4 ra0[TA::PIECES], rb0[TB::PIECES], ra1[TA::PIECES], rb1[TB::PIECES];
+    TA::load(ra0, A, p.lda, m0, p.M, k_begin, k_end, p.K, tid);
+    TB::load(rb0, B, p.ldb, n0, p.N, k_begin, k_end, p.K, tid);
+    TA::load(ra1, A, p.lda, m0, p.M, k_begin + BK, k_end, p.K, tid);
+    TB::load(rb1, B, p.ldb, n0, p.N, k_begin + BK, k_end, p.K, tid);
+    TA::store(lds, ra0, tid);
+    TB::store(lds + TA::ELEMS, rb0, tid);
     __syncthreads();
+    auto iteration = [&](const bf16* As, bf16* An, uint4 (&la)[TA::PIECES], uint4 (&lb)[TB::PIECES],
+                         uint4 (&sa)[TA::PIECES], uint4 (&sb)[TB::PIECES], int k0) {
+      // loads into (la, lb) for chunk k0; stores from (sa, sb), loaded an iteration ago
+      read(As, 0, fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      read(As, 1, fa1, fb1);
+      TA::load(la, A, p.lda, m0, p.M, k0, k_end, p.K, tid);
+      TB::load(lb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
+      mma(fa0, fb0);
+      sched_phase<NMMA, NDSR, NVM, 0>();
+      read(As, 2, fa0, fb0);
+      mma(fa1, fb1);
+      sched_phase<NMMA, NDSR, 0, 0>();
+      read(As, 3, fa1, fb1);
+      mma(fa0, fb0);
+      TA::store(An, sa, tid);
+      sched_phase<NMMA, NDSR, 0, TA::PIECES>();
+      mma(fa1, fb1);
+      TB::store(An + TA::ELEMS, sb, tid);
+      sched_phase<NMMA, 0, 0, TB::PIECES>();
+      __syncthreads();
+    };
+    for (int kc = 0; kc < nk; kc += 2) {
+      iteration(lds, lds + STAGE, ra0, rb0, ra1, rb1, k_begin + (kc + 2) * BK);
+      // an all-zero chunk when nk is odd
+      iteration(lds + STAGE, lds, ra1, rb1, ra0, rb0, k_begin + (kc + 3) * BK);
+    }
   }
 
   // ---- epilogue: accumulators -> per-wave LDS staging -> contiguous row stores ----
@@ -208,8 +292,10 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   a.tiles_n = (a.N + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, A_KC, B_KC, OutT, COLSUM>), dim3((unsigned)grid),
-                     dim3(256), 0, s, a);
+  // big tiles have no registers to spare for a second set of loads in flight
+  constexpr int PF = (BM * BN >= 256 * 256) ? 1 : 2;
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, A_KC, B_KC, OutT, COLSUM, PF>),
+                     dim3((unsigned)grid), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -15,44 +15,84 @@
 namespace sk {
 
 constexpr int BK = 64;           // k extent of one LDS chunk
-constexpr int KC_LD = BK + 8;    // LDS row stride (elements) of a k-contiguous tile:
-                                 // 144 bytes, so 16 consecutive rows start 4 banks apart
-                                 // modulo 64 and a 16-byte-per-lane read is conflict free
 
-// One operand tile of EXT rows (m or n extent) by BK in LDS.
-//   KC  = true : source is [EXT, K] with k contiguous; stored [EXT][KC_LD].
-//   KC  = false: source is [K, EXT] with m/n contiguous; stored [BK][EXT + 32] and
+// A window onto a dense row-major global array, as a raw buffer resource: loads
+// through it take a 32-bit byte offset from the window's origin and return zero
+// for any offset at or past the end of the array, so ragged edges need no branch
+// (a lane that must read zero for another reason is pointed past the end).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned OOB_OFFSET = 0x80000000u;
+
+struct GWindow {
+  __amdgpu_buffer_rsrc_t rsrc;
+};
+
+// Window starting `origin` elements into an array of `total` elements of `esize` bytes.
+__device__ __forceinline__ GWindow make_window(const void* base, int64_t origin, int64_t total,
+                                               int esize) {
+  int64_t bytes = (total - origin) * esize;
+  if (bytes < 0) bytes = 0;
+  if (bytes > 0x7fffffff) bytes = 0x7fffffff;
+  GWindow w;
+  w.rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(static_cast<const char*>(base)) + origin * esize, 0, (int)bytes, 0x00020000);
+  return w;
+}
+
+__device__ __forceinline__ uint4 window_load16(const GWindow& w, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, (int)byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// One operand tile of EXT rows (m or n extent) by KX (k extent, default BK) in LDS.
+//   KC  = true : source is [EXT, K] with k contiguous; stored [EXT][KX] without padding,
+//                the 16-byte pieces of each row XOR-swizzled by the row number
+//                (kc_piece): a store instruction then fills whole 256-byte bank rows
+//                and the 16 rows a fragment read touches per pass land in 16 different
+//                bank groups -- both conflict free.
+//   KC  = false: source is [K, EXT] with m/n contiguous; stored [KX][EXT + 32] and
 //                read through the LDS transpose read (ds_read_b64_tr_b16).  The row
 //                stride is 16 dwords modulo 32, so the four k rows a 16-lane group
 //                reads sit in disjoint banks.
-template <int EXT, bool KC>
-struct OpTile {
-  static constexpr int LD = KC ? KC_LD : EXT + 32;
-  static constexpr int ELEMS = KC ? EXT * KC_LD : BK * (EXT + 32);
-  static constexpr int PIECES = EXT / 32;  // 16-byte pieces per thread per chunk (256 threads)
+// Physical position of logical 16-byte piece `pc` of row `row` in a k-contiguous tile
+// whose rows hold KX elements (KX / 8 pieces, a power of two up to 32).  Rows that
+// share a 256-byte bank row get different XOR keys, as do the 16 consecutive rows of
+// one fragment-read pass.
+template <int KX>
+__device__ __forceinline__ int kc_piece(int row, int pc) {
+  constexpr int PPR = KX / 8;
+  constexpr int ROWS_PER_BANKROW = PPR >= 16 ? 1 : 16 / PPR;
+  return pc ^ ((row / ROWS_PER_BANKROW) & (PPR - 1));
+}
 
-  // Global -> registers.  `ext0` is the tile's first row/col, `ext_total` the
-  // array's extent in that dimension; k in [k0, k0 + BK) is clipped at k_end.
-  // Everything outside is read as zero.  Extents along a contiguous dimension
-  // are multiples of 8, so a 16-byte piece is wholly inside or wholly outside.
+template <int EXT, bool KC, int KX = BK>
+struct OpTile {
+  static constexpr int LD = KC ? KX : EXT + 32;
+  static constexpr int ELEMS = KC ? EXT * KX : KX * (EXT + 32);
+  static constexpr int PIECES = EXT * KX / 2048;  // 16-byte pieces per thread (256 threads)
+  static_assert(EXT * KX % 2048 == 0, "tile must split evenly over 256 threads");
+
+  // Global -> registers, branch free.  `g` is the whole array ([ext_total, k_total]
+  // for KC, [k_total, ext_total] otherwise, row stride ld).  The tile starts at
+  // row/col ext0 and k0; k is clipped at k_end and ext at ext_total; everything
+  // outside reads as zero.  Extents along a contiguous dimension are multiples of
+  // 8, so a 16-byte piece is wholly inside or wholly outside.
   static __device__ __forceinline__ void load(uint4 (&r)[PIECES], const bf16* __restrict__ g,
                                               int64_t ld, int ext0, int ext_total, int k0,
-                                              int k_end, int tid) {
+                                              int k_end, int k_total, int tid) {
+    const int64_t rows = KC ? ext_total : k_total;
+    const int64_t origin = KC ? (int64_t)ext0 * ld + k0 : (int64_t)k0 * ld + ext0;
+    const GWindow w = make_window(g, origin, rows * ld, 2);
+    const unsigned ldb = (unsigned)ld * 2u;
 #pragma unroll
     for (int p = 0; p < PIECES; ++p) {
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (KC) {
-        const int e = ext0 + p * 32 + (tid >> 3);
-        const int kk = k0 + (tid & 7) * 8;
-        if (e < ext_total && kk < k_end) v = *reinterpret_cast<const uint4*>(g + (int64_t)e * ld + kk);
-      } else {
-        constexpr int PPR = EXT / 8;
-        const int piece = p * 256 + tid;
-        const int kk = k0 + piece / PPR;
-        const int e = ext0 + (piece % PPR) * 8;
-        if (e < ext_total && kk < k_end) v = *reinterpret_cast<const uint4*>(g + (int64_t)kk * ld + e);
-      }
-      r[p] = v;
+      const int piece = p * 256 + tid;
+      constexpr int PPR = KC ? KX / 8 : EXT / 8;
+      const int row = piece / PPR, col = (piece % PPR) * 8;
+      // rows past the end of the array fall outside the window by themselves
+      const bool ok = KC ? (k0 + col < k_end) : (ext0 + col < ext_total && k0 + row < k_end);
+      const unsigned off = (unsigned)row * ldb + (unsigned)col * 2u;
+      r[p] = window_load16(w, ok ? off : OOB_OFFSET);
     }
   }
 
@@ -60,13 +100,11 @@ struct OpTile {
   static __device__ __forceinline__ void store(bf16* tile, const uint4 (&r)[PIECES], int tid) {
 #pragma unroll
     for (int p = 0; p < PIECES; ++p) {
-      if (KC) {
-        *reinterpret_cast<uint4*>(tile + (p * 32 + (tid >> 3)) * LD + (tid & 7) * 8) = r[p];
-      } else {
-        constexpr int PPR = EXT / 8;
-        const int piece = p * 256 + tid;
-        *reinterpret_cast<uint4*>(tile + (piece / PPR) * LD + (piece % PPR) * 8) = r[p];
-      }
+      const int piece = p * 256 + tid;
+      constexpr int PPR = KC ? KX / 8 : EXT / 8;
+      const int row = piece / PPR;
+      const int pc = KC ? kc_piece<KX>(row, piece % PPR) : piece % PPR;
+      *reinterpret_cast<uint4*>(tile + row * LD + pc * 8) = r[p];
     }
   }
 };
@@ -78,7 +116,8 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 template <bool KC, int LD>
 __device__ __forceinline__ bf16x8 read_frag(const bf16* tile, int e0, int ks, int lane) {
   if (KC) {
-    return *reinterpret_cast<const bf16x8*>(tile + (e0 + (lane & 31)) * LD + ks * 16 + (lane >> 5) * 8);
+    const int row = e0 + (lane & 31);
+    return *reinterpret_cast<const bf16x8*>(tile + row * LD + kc_piece<LD>(row, ks * 2 + (lane >> 5)) * 8);
   } else {
     // ds_read_b64_tr_b16, per group of 16 lanes: lane i receives, as element e,
     // element (i % 4) of what lane 4 e + i / 4 of the group addressed.  With lane j
@@ -93,6 +132,13 @@ __device__ __forceinline__ bf16x8 read_frag(const bf16* tile, int e0, int ks, in
     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, both);
   }
+}
+
+// Fragment of a plain row-major [rows][LD] bf16 tile (k contiguous, rows padded by the
+// caller so that LD / 2 is 4 modulo 8 dwords): 16 bytes per lane, no swizzle.
+template <int LD>
+__device__ __forceinline__ bf16x8 read_frag_rowmajor(const bf16* tile, int e0, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + (e0 + (lane & 31)) * LD + ks * 16 + (lane >> 5) * 8);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {

@@ -48,7 +48,9 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
   unsigned char* const ostage = work + 2 * TB2::ELEMS * 2;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tile_m = blockIdx.x / p.n_slices, slice = blockIdx.x % p.n_slices;
+  // all slices of one token tile run on the same XCD, so its L2 fetches the tile once
+  const int wg = xcd_remap(blockIdx.x, p.tiles_m * p.n_slices);
+  const int tile_m = wg / p.n_slices, slice = wg % p.n_slices;
   const int m0 = tile_m * CH_BM;
 
   // this work-group's run of BN-wide tiles
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
   const bf16* __restrict__ B2 = static_cast<const bf16*>(p.B2);
   uint4 rb[TB2::PIECES];
   // first B2 chunk goes in flight before anything else
-  TB2::load(rb, B2, p.ldb2, t_begin * BN, p.N, 0, p.R, tid);
+  TB2::load(rb, B2, p.ldb2, t_begin * BN, p.N, 0, p.R, p.R, tid);
 
   // ---------------- the intermediate tile Zt -> LDS ----------------
   if (FUSED) {
@@ -81,8 +83,8 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
       for (int r = 0; r < 16; ++r) acc1[j][r] = 0.f;
     uint4 ra[TA::PIECES], rb1[TB1::PIECES];
     const int nk = (p.K1 + BK - 1) / BK;
-    TA::load(ra, A, p.lda, m0, p.M, 0, p.K1, tid);
-    TB1::load(rb1, B1, p.ldb1, 0, p.R, 0, p.K1, tid);
+    TA::load(ra, A, p.lda, m0, p.M, 0, p.K1, p.K1, tid);
+    TB1::load(rb1, B1, p.ldb1, 0, p.R, 0, p.K1, p.K1, tid);
     TA::store(s1, ra, tid);
     TB1::store(s1 + TA::ELEMS, rb1, tid);
     __syncthreads();
@@ -91,8 +93,8 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
       const bf16* Bs = As + TA::ELEMS;
       const bool more = kc + 1 < nk;
       if (more) {
-        TA::load(ra, A, p.lda, m0, p.M, (kc + 1) * BK, p.K1, tid);
-        TB1::load(rb1, B1, p.ldb1, 0, p.R, (kc + 1) * BK, p.K1, tid);
+        TA::load(ra, A, p.lda, m0, p.M, (kc + 1) * BK, p.K1, p.K1, tid);
+        TB1::load(rb1, B1, p.ldb1, 0, p.R, (kc + 1) * BK, p.K1, p.K1, tid);
       }
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int ks = 0; ks < RT / 16; ++ks)
-      fa[i][ks] = read_frag<true, L::Z_LD>(Zs, i * 32, ks, lane);
+      fa[i][ks] = read_frag_rowmajor<L::Z_LD>(Zs, i * 32, ks, lane);
 
   TB2::store(Bbuf, rb, tid);
   __syncthreads();
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
       if (more) {
         const int nn0 = (c + 1 < KC) ? n0 : n0 + BN;
         const int k0 = (c + 1 < KC) ? (c + 1) * 64 : 0;
-        TB2::load(rb, B2, p.ldb2, nn0, p.N, k0, p.R, tid);
+        TB2::load(rb, B2, p.ldb2, nn0, p.N, k0, p.R, p.R, tid);
       }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
@@ -249,6 +251,266 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Narrow sketches (R <= 128): the same chain, shaped for memory-level parallelism.
+// These shapes are bound by bytes, not flops, so the kernel keeps two loads in
+// flight per thread at all times (two register sets, prefetch distance two) and is
+// small enough in LDS and registers for two work-groups per CU.
+//   - waves 2 x 2: wave (wm, wn) owns rows 32 wm.. of the token tile throughout;
+//   - stage 1 walks K1 in 64-wide chunks (x chunk + B1 chunk per step);
+//   - stage 2 takes B2 one whole [R x 64] tile at a time (no k loop inside a tile):
+//     each wave does R/16 MFMAs on two interleaved accumulators per tile.
+// ---------------------------------------------------------------------------
+constexpr int CS_BN = 64;
+
+template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
+struct SmallLds {
+  typedef OpTile<CS_BN, B2_KC, RT> TB2;
+  typedef OpTile<CH_BM, true> TA;
+  typedef OpTile<RT, B1_KC> TB1;
+  static constexpr int Z_LD = RT + 8;
+  static constexpr int Z_BYTES = CH_BM * Z_LD * 2;
+  static constexpr int OUT_LD = CS_BN * 2 + 8;
+  static constexpr int S2_BYTES = 2 * TB2::ELEMS * 2 + CH_BM * OUT_LD;
+  static constexpr int S1_BYTES = FUSED ? 2 * (TA::ELEMS + TB1::ELEMS) * 2 : 0;
+  static constexpr int BYTES = Z_BYTES + (S1_BYTES > S2_BYTES ? S1_BYTES : S2_BYTES);
+};
+
+template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
+__global__ __launch_bounds__(256, 2) void chain_small_kernel(const ChainArgs p) {
+  typedef SmallLds<RT, B2_KC, FUSED, B1_KC> L;
+  typedef typename L::TB2 TB2;
+  constexpr int KS = RT / 16;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[L::BYTES];
+  bf16* const Zs = reinterpret_cast<bf16*>(smem);
+  unsigned char* const work = smem + L::Z_BYTES;
+  bf16* const Bbuf = reinterpret_cast<bf16*>(work);
+  unsigned char* const ostage = work + 2 * TB2::ELEMS * 2;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int wg = xcd_remap(blockIdx.x, p.tiles_m * p.n_slices);
+  const int tile_m = wg / p.n_slices, slice = wg % p.n_slices;
+  const int m0 = tile_m * CH_BM;
+
+  const int n_tiles = (p.N + CS_BN - 1) / CS_BN;
+  const int per_slice = (n_tiles + p.n_slices - 1) / p.n_slices;
+  const int t_begin = slice * per_slice;
+  const int t_end = (t_begin + per_slice < n_tiles) ? t_begin + per_slice : n_tiles;
+  const int my_tiles = t_end - t_begin;
+  if (my_tiles <= 0) return;  // uniform over the work-group
+
+  const bf16* __restrict__ B2 = static_cast<const bf16*>(p.B2);
+  uint4 rb0[TB2::PIECES], rb1[TB2::PIECES];
+  // B2 tile jt of this work-group; tiles past its run load as zeros (all lanes masked)
+  auto load_b2 = [&](uint4 (&r)[TB2::PIECES], int jt) {
+    TB2::load(r, B2, p.ldb2, (t_begin + jt) * CS_BN, jt < my_tiles ? p.N : 0, 0, p.R, p.R, tid);
+  };
+  // the first two B2 tiles go in flight before anything else
+  load_b2(rb0, 0);
+  load_b2(rb1, 1);
+
+  // ---------------- the intermediate tile Zt -> LDS ----------------
+  if (FUSED) {
+    typedef typename L::TA TA;
+    typedef typename L::TB1 TB1;
+    constexpr int STAGE = TA::ELEMS + TB1::ELEMS;
+    constexpr int TN1 = RT / 64;
+    bf16* const s1 = reinterpret_cast<bf16*>(work);
+    const bf16* __restrict__ A = static_cast<const bf16*>(p.A);
+    const bf16* __restrict__ B1 = static_cast<const bf16*>(p.B1);
+    f32x16 acc1[TN1];
+#pragma unroll
+    for (int j = 0; j < TN1; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc1[j][r] = 0.f;
+    uint4 xa0[TA::PIECES], xb0[TB1::PIECES], xa1[TA::PIECES], xb1[TB1::PIECES];
+    const int nk = (p.K1 + BK - 1) / BK;
+    // chunks past K1 load as zeros, so the loop needs no branch around its loads
+    auto load0 = [&](int kc) {
+      TA::load(xa0, A, p.lda, m0, p.M, kc * BK, p.K1, p.K1, tid);
+      TB1::load(xb0, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
+    };
+    auto load1 = [&](int kc) {
+      TA::load(xa1, A, p.lda, m0, p.M, kc * BK, p.K1, p.K1, tid);
+      TB1::load(xb1, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
+    };
+    auto compute = [&](const bf16* As) {
+      const bf16* Bs = As + TA::ELEMS;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        const bf16x8 fa = read_frag<true, TA::LD>(As, wm * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < TN1; ++j) {
+          const bf16x8 fb = read_frag<B1_KC, TB1::LD>(Bs, wn * (RT / 2) + j * 32, ks, lane);
+          acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc1[j], 0, 0, 0);
+        }
+      }
+    };
+    load0(0);
+    load1(1);
+    TA::store(s1, xa0, tid);
+    TB1::store(s1 + TA::ELEMS, xb0, tid);
+    __syncthreads();
+    for (int kc = 0; kc < nk; kc += 2) {
+      // chunk kc sits in buffer 0; set 1 holds chunk kc + 1 (in flight or landed)
+      load0(kc + 2);
+      __builtin_amdgcn_sched_barrier(0);  // keep the new loads ahead of the wait for the old ones
+      compute(s1);
+      __builtin_amdgcn_sched_barrier(0);
+      TA::store(s1 + STAGE, xa1, tid);
+      TB1::store(s1 + STAGE + TA::ELEMS, xb1, tid);
+      __syncthreads();
+      load1(kc + 3);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(s1 + STAGE);  // an all-zero chunk when nk is odd
+      __builtin_amdgcn_sched_barrier(0);
+      TA::store(s1, xa0, tid);
+      TB1::store(s1 + TA::ELEMS, xb0, tid);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < TN1; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = wn * (RT / 2) + j * 32 + q * 8 + (lane >> 5) * 4;
+        uint2 w;
+        w.x = pack_bf16x2(acc1[j][q * 4 + 0], acc1[j][q * 4 + 1]);
+        w.y = pack_bf16x2(acc1[j][q * 4 + 2], acc1[j][q * 4 + 3]);
+        *reinterpret_cast<uint2*>(Zs + (wm * 32 + (lane & 31)) * L::Z_LD + c) = w;
+      }
+  } else if (p.z_splits == 0) {
+    const bf16* __restrict__ Z = static_cast<const bf16*>(p.Z);
+    constexpr int PPR = RT / 8;
+#pragma unroll
+    for (int i = 0; i < (CH_BM * PPR) / 256; ++i) {
+      const int piece = i * 256 + tid;
+      const int r = piece / PPR, c = (piece % PPR) * 8;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (m0 + r < p.M && c < p.R) v = *reinterpret_cast<const uint4*>(Z + (int64_t)(m0 + r) * p.R + c);
+      *reinterpret_cast<uint4*>(Zs + r * L::Z_LD + c) = v;
+    }
+  } else {
+    // sum of fp32 split-K slabs in index order, rounded once to bf16; all loads of a
+    // piece are issued before the first add
+    const float* __restrict__ Zp = static_cast<const float*>(p.Z);
+    constexpr int PPR = RT / 4;
+    constexpr int MAXS = 8;
+#pragma unroll
+    for (int i = 0; i < (CH_BM * PPR) / 256; ++i) {
+      const int piece = i * 256 + tid;
+      const int r = piece / PPR, c = (piece % PPR) * 4;
+      float4 v[MAXS];
+      const bool ok = m0 + r < p.M && c < p.R;
+      const float* src = Zp + (int64_t)(m0 + r) * p.R + c;
+#pragma unroll
+      for (int k = 0; k < MAXS; ++k) {
+        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok && k < p.z_splits) v[k] = *reinterpret_cast<const float4*>(src + (int64_t)k * p.z_slab);
+      }
+      float4 s = v[0];
+#pragma unroll
+      for (int k = 1; k < MAXS; ++k) { s.x += v[k].x; s.y += v[k].y; s.z += v[k].z; s.w += v[k].w; }
+      uint2 w;
+      w.x = pack_bf16x2(s.x, s.y);
+      w.y = pack_bf16x2(s.z, s.w);
+      *reinterpret_cast<uint2*>(Zs + r * L::Z_LD + c) = w;
+    }
+  }
+  __syncthreads();  // Zt complete; stage-1 buffers (aliasing Bbuf) are free
+
+  // this wave's 32 rows of Zt, as MFMA fragments, for the rest of the kernel
+  bf16x8 fa[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) fa[ks] = read_frag_rowmajor<L::Z_LD>(Zs, wm * 32, ks, lane);
+
+  TB2::store(Bbuf, rb0, tid);
+  __syncthreads();
+
+  bf16* __restrict__ C = static_cast<bf16*>(p.C);
+  const float scale = p.scale;
+  // bias through a buffer window of N elements (zero elements when there is no bias:
+  // every load then returns zero)
+  const GWindow bias_w = make_window(p.bias, 0, p.bias != nullptr ? p.N : 0, 2);
+
+  // this lane's 4 x 4 bias values of tile jt (issued before the prefetch of B2, so the
+  // epilogue does not have to wait for that prefetch to land)
+  auto load_bias = [&](uint2 (&bv)[4], int jt) {
+    const int n0 = (t_begin + jt) * CS_BN;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int cc = wn * 32 + q * 8 + (lane >> 5) * 4;
+      typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(bias_w.rsrc, (n0 + cc) * 2, 0, 0);
+      bv[q] = make_uint2(v.x, v.y);
+    }
+  };
+
+  auto tile = [&](int jt, const bf16* Bs, const uint2 (&bv)[4]) {
+    f32x16 a0, a1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks += 2) {
+      const bf16x8 f0 = read_frag<B2_KC, TB2::LD>(Bs, wn * 32, ks, lane);
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, fa[ks], a0, 0, 0, 0);
+      if (ks + 1 < KS) {
+        const bf16x8 f1 = read_frag<B2_KC, TB2::LD>(Bs, wn * 32, ks + 1, lane);
+        a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, fa[ks + 1], a1, 0, 0, 0);
+      }
+    }
+    const int n0 = (t_begin + jt) * CS_BN;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int cc = wn * 32 + q * 8 + (lane >> 5) * 4;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (a0[q * 4 + e] + a1[q * 4 + e]) * scale;
+      v[0] += bf16_bits_to_float(bv[q].x & 0xffffu);
+      v[1] += bf16_bits_to_float(bv[q].x >> 16);
+      v[2] += bf16_bits_to_float(bv[q].y & 0xffffu);
+      v[3] += bf16_bits_to_float(bv[q].y >> 16);
+      uint2 w;
+      w.x = pack_bf16x2(v[0], v[1]);
+      w.y = pack_bf16x2(v[2], v[3]);
+      *reinterpret_cast<uint2*>(ostage + (wm * 32 + (lane & 31)) * L::OUT_LD + cc * 2) = w;
+    }
+    __syncthreads();
+    constexpr int PPR = CS_BN / 8;  // 16-byte pieces per output row
+    const int n_lim = jt < my_tiles ? p.N : 0;
+#pragma unroll
+    for (int s = 0; s < (CH_BM * PPR) / 256; ++s) {
+      const int idx = s * 256 + tid;
+      const int r = idx / PPR, pc = idx % PPR;
+      const int gm = m0 + r, gn = n0 + pc * 8;
+      if (gm < p.M && gn < n_lim) {
+        const uint2 lo = *reinterpret_cast<const uint2*>(ostage + r * L::OUT_LD + pc * 16);
+        const uint2 hi = *reinterpret_cast<const uint2*>(ostage + r * L::OUT_LD + pc * 16 + 8);
+        *reinterpret_cast<uint4*>(C + (int64_t)gm * p.ldc + gn) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+    }
+  };
+
+  for (int jt = 0; jt < my_tiles; jt += 2) {
+    // tile jt sits in buffer 0; set 1 holds tile jt + 1
+    uint2 bv[4];
+    load_bias(bv, jt);
+    load_b2(rb0, jt + 2);
+    __builtin_amdgcn_sched_barrier(0);  // keep the new loads ahead of the wait for the old ones
+    tile(jt, Bbuf, bv);
+    __builtin_amdgcn_sched_barrier(0);
+    TB2::store(Bbuf + TB2::ELEMS, rb1, tid);
+    __syncthreads();
+    load_bias(bv, jt + 1);
+    load_b2(rb1, jt + 3);
+    __builtin_amdgcn_sched_barrier(0);
+    tile(jt + 1, Bbuf + TB2::ELEMS, bv);  // computes on zeros and stores nothing past the run
+    __builtin_amdgcn_sched_barrier(0);
+    TB2::store(Bbuf, rb0, tid);
+    __syncthreads();
+  }
+}
+
 bool chain_supported(int R) { return R >= 16 && R <= 512; }
 
 template <int RT, int BN, bool B2_KC, bool FUSED, bool B1_KC>
@@ -260,11 +522,21 @@ static hipError_t launch_one(const ChainArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
+static hipError_t launch_small(const ChainArgs& a, hipStream_t s) {
+  const long long grid = (long long)a.tiles_m * a.n_slices;
+  if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((chain_small_kernel<RT, B2_KC, FUSED, B1_KC>), dim3((unsigned)grid), dim3(256),
+                     0, s, a);
+  return hipGetLastError();
+}
+
 template <bool B_KC, bool FUSED>
 static hipError_t launch_rt(const ChainArgs& a, hipStream_t s) {
   constexpr int BN = 128;
-  if (a.R <= 64) return launch_one<64, BN, B_KC, FUSED, B_KC>(a, s);
-  if (a.R <= 128) return launch_one<128, BN, B_KC, FUSED, B_KC>(a, s);
+  if (a.z_splits > 8) return hipErrorInvalidValue;
+  if (a.R <= 64) return launch_small<64, B_KC, FUSED, B_KC>(a, s);
+  if (a.R <= 128) return launch_small<128, B_KC, FUSED, B_KC>(a, s);
   if (a.R <= 192) return launch_one<192, BN, B_KC, FUSED, B_KC>(a, s);
   if (a.R <= 256) return launch_one<256, BN, B_KC, FUSED, B_KC>(a, s);
   if (!FUSED) {  // the fused form needs LDS for both stages: R <= 256 only
@@ -274,7 +546,7 @@ static hipError_t launch_rt(const ChainArgs& a, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
-int chain_bn() { return 128; }
+int chain_bn(int R) { return R <= 128 ? CS_BN : 128; }
 
 hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s) {
   if (!chain_supported(a.R) || a.n_slices < 1 || (fused && a.R > CHAIN_FUSED_MAX_R))

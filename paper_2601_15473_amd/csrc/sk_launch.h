@@ -59,7 +59,7 @@ struct ChainArgs {
 };
 bool chain_supported(int R);
 constexpr int CHAIN_FUSED_MAX_R = 256;
-int chain_bn();
+int chain_bn(int R);   // width of the N tiles the chain kernels walk
 hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s);
 
 }  // namespace sk
