@@ -25,8 +25,14 @@ FLAGS = [
 ]
 
 
+# Per-source extras.  The chain kernels read every accumulator exactly once in their
+# epilogues, so MFMA results go straight to VGPRs there (the option crashes this
+# compiler on the 256x256 GEMM, whose accumulators need the AGPR file anyway).
+EXTRA = {"sk_chain.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _compile(src: str, obj: str) -> None:
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines()
                     if "packed-fp32-ops" not in l and "not a recognized feature" not in l)

@@ -68,37 +68,40 @@ struct WeightPlan {
   int tile;
   int splits;
   int k_per_split;
+  int64_t ldz;         // bf16: row stride of Z^T [R, ldz]
   size_t z_bytes, part_bytes, csum_bytes;
   size_t total() const { return z_bytes + part_bytes + csum_bytes; }
 };
 
-// Split of the token contraction of dU = Z^T . dY: enough work-groups to fill the
-// chip, at least 256 tokens per split, splits in a fixed order (deterministic sum).
+// Split of the token contraction of dU = Z^T . dY.  The output (R x out, fp32) is
+// small, and every split writes and re-reads a slab of it, so: as few splits as fill
+// the chip, at least 256 tokens each, summed in a fixed order (deterministic).
 WeightPlan plan_weight(const Shape& s) {
   WeightPlan w{};
   int bm, bn;
   if (s.dtype == SK_BF16) {
-    // the output (R x out) is small: prefer small tiles and few splits, since every
-    // split writes and re-reads a full fp32 slab of it
-    w.tile = (s.R >= 128 && s.out >= 128 && ((s.R + 127) / 128) * ((s.out + 127) / 128) >= NUM_CUS)
-                 ? TILE_128x128 : TILE_64x64;
+    w.tile = s.R > 64 ? TILE_128x64 : TILE_64x64;
+    if (((s.R + 127) / 128) * ((s.out + 127) / 128) >= NUM_CUS) w.tile = TILE_128x128;
     tile_dims(w.tile, bm, bn);
+    w.ldz = (s.T + 63) / 64 * 64;
+    w.z_bytes = align_up((size_t)s.R * w.ldz * 2);
   } else {
     w.tile = -1;
     bm = F32_BM; bn = F32_BN;
+    w.ldz = s.R;
+    w.z_bytes = align_up((size_t)s.T * s.R * 4);
   }
   const int64_t tiles = ((s.R + bm - 1) / bm) * ((s.out + bn - 1) / bn);
-  int64_t splits = (2 * NUM_CUS + tiles - 1) / tiles;
+  int64_t splits = NUM_CUS / tiles;   // one wave of work-groups: no half-empty second round
   const int64_t max_splits = (s.T + 255) / 256;
   if (splits > max_splits) splits = max_splits;
-  if (splits > 64) splits = 64;
+  if (splits > 32) splits = 32;
   if (splits < 1) splits = 1;
   int64_t kps = (s.T + splits - 1) / splits;
   kps = (kps + 63) / 64 * 64;
   splits = (s.T + kps - 1) / kps;
   w.splits = (int)splits;
   w.k_per_split = (int)kps;
-  w.z_bytes = align_up((size_t)s.T * s.R * s.esize);
   w.part_bytes = splits > 1 ? align_up((size_t)splits * s.R * s.out * 4) : 0;
   w.csum_bytes = splits > 1 ? align_up((size_t)splits * s.out * 4) : 0;
   return w;
@@ -113,7 +116,7 @@ enum Plan : int {
                           // sums them on the way into LDS (bf16, R <= 512)
 };
 
-Plan pick_plan(const Shape& s) {
+Plan pick_plan(const Shape& s, sk_op op) {
   const int forced = g_plan.load(std::memory_order_relaxed);
   const bool chain_ok = s.dtype == SK_BF16 && chain_supported(s.R);
   const bool fused_ok = chain_ok && s.R <= CHAIN_FUSED_MAX_R;
@@ -123,8 +126,12 @@ Plan pick_plan(const Shape& s) {
     case PLAN_SPLIT_EXPAND: return chain_ok ? PLAN_SPLIT_EXPAND : PLAN_TWO_GEMM;
     default: break;
   }
-  // automatic: the on-chip plans pay off while the layer is bandwidth bound
-  if (chain_ok && s.R <= 256) return PLAN_SPLIT_EXPAND;
+  // automatic (measured on MI355X): the on-chip plans win while the sketch is narrow
+  // (R <= 128: the layer is bound by bytes and by launch count); wider sketches run
+  // faster as two general GEMMs with large tiles.  Forward fuses (its first
+  // contraction is short, so recomputing it per N slice is cheap); the input gradient's
+  // first contraction runs over `out`, too long to recompute, so it is split instead.
+  if (chain_ok && s.R <= 128) return op == SK_OP_FWD ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
   return PLAN_TWO_GEMM;
 }
 
@@ -156,11 +163,11 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
   return q;
 }
 
-// Number of N slices of the expand/fused kernel: about two work-groups per CU.
+// Number of N slices of the expand/fused kernel: one work-group per CU.
 int chain_slices(int64_t T, int64_t N, int R) {
   const int64_t tiles_m = (T + 63) / 64;
   const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
-  int64_t sl = (2 * NUM_CUS + tiles_m - 1) / tiles_m;
+  int64_t sl = NUM_CUS / tiles_m;
   if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
@@ -248,7 +255,7 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
   const float scale = 1.0f / (float)l;
   g_hip_error.clear();
 
-  const Plan plan = pick_plan(s);
+  const Plan plan = pick_plan(s, SK_OP_FWD);
   if (plan != PLAN_FUSED && (!workspace || workspace_bytes < workspace_for(SK_OP_FWD, s)))
     return SK_ERR_WORKSPACE;
   if (plan == PLAN_FUSED || plan == PLAN_SPLIT_EXPAND) {
@@ -291,7 +298,7 @@ sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_c
   const float scale = 1.0f / (float)l;
   g_hip_error.clear();
 
-  const Plan plan = pick_plan(s);
+  const Plan plan = pick_plan(s, SK_OP_BWD_INPUT);
   if (plan != PLAN_FUSED && (!workspace || workspace_bytes < workspace_for(SK_OP_BWD_INPUT, s)))
     return SK_ERR_WORKSPACE;
   if (plan == PLAN_FUSED || plan == PLAN_SPLIT_EXPAND) {
@@ -341,13 +348,24 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
   float* part = reinterpret_cast<float*>(ws + w.z_bytes);
   float* cpart = reinterpret_cast<float*>(ws + w.z_bytes + w.part_bytes);
 
-  // Z = x . S_cat, recomputed here rather than kept from the forward pass
-  hipError_t e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+  // Z = x . S_cat is recomputed here rather than kept from the forward pass.  In bf16
+  // it is produced transposed (Z^T = S_cat^T . x^T, [R, ldz] with zero-filled row
+  // padding) so that the token contraction below reads it k-contiguous.
+  GemmArgs a{};
+  hipError_t e;
+  if (s.dtype == SK_BF16) {
+    GemmArgs z = dense_args(S_cat, s.R, x, in, Z, w.ldz, s.R, tokens, in, 1.0f, nullptr);
+    z.n_store = (int)w.ldz;
+    e = launch_gemm_bf16(GEMM_TT, choose_tile(s.R, tokens, 1), z, hs);
+    a.A = Z; a.lda = w.ldz;
+  } else {
+    e = launch_gemm_f32(GEMM_NN, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+    a.A = Z; a.lda = s.R;
+  }
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (x.S)");
 
   // dU = scale * Z^T . dY and db = column sums of dY, the token axis split in order
-  GemmArgs a{};
-  a.A = Z; a.B = dY; a.lda = s.R; a.ldb = out; a.ldc = out;
+  a.B = dY; a.ldb = out; a.ldc = out;
   a.M = s.R; a.N = (int)out; a.K = (int)tokens;
   a.splits = w.splits; a.k_per_split = w.k_per_split;
   a.bias = nullptr;
@@ -356,18 +374,16 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
   } else {
     a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
   }
-  e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_TN_F32, w.tile, a, hs)
+  e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs)
                          : launch_gemm_f32(GEMM_TN_F32, a, hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (Z^T.dY)");
   if (w.splits > 1) {
-    ReduceArgs r{part, dU_cat, (int64_t)s.R * out, w.splits, scale};
+    ReduceArgs r{};
+    r.part = part; r.out = dU_cat; r.n = (int64_t)s.R * out; r.scale = scale;
+    r.part2 = cpart; r.out2 = dbias; r.n2 = dbias ? out : 0; r.scale2 = 1.0f;
+    r.splits = w.splits;
     e = launch_reduce_splits(r, hs);
-    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (reduce dU)");
-    if (dbias) {
-      ReduceArgs rb{cpart, dbias, out, w.splits, 1.0f};
-      e = launch_reduce_splits(rb, hs);
-      if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (reduce db)");
-    }
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (sum of splits)");
   }
   return SK_OK;
 }

@@ -206,6 +206,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
   const bf16* __restrict__ bias = static_cast<const bf16*>(p.bias);
   const float scale = p.scale;
   const int wn0 = n0 + wn * WN;  // first global column of this wave
+  const int n_store = p.n_store > 0 ? p.n_store : p.N;
   constexpr int PPR = WN * (int)sizeof(OutT) / PIECE;  // pieces per staged row
 
 #pragma unroll
@@ -243,7 +244,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
       const int idx = it * 64 + lane;
       const int r = idx / PPR, pc = idx % PPR;
       const int gm = row_base + r, gn = wn0 + pc * 4;
-      if (gm < p.M && gn < p.N) {
+      if (gm < p.M && gn < n_store) {
         if (sizeof(OutT) == 2) {
           const uint2 w = *reinterpret_cast<const uint2*>(stage + r * EP_LD + pc * PIECE);
           *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(C) + (int64_t)gm * p.ldc + gn) = w;
@@ -273,17 +274,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
   }
 }
 
-// out[i] = scale * sum over splits of part[s][i], splits added in index order.
+// Sums the split-K slabs in index order; see ReduceArgs.
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const ReduceArgs p) {
-  const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-  if (i4 >= p.n) return;
-  float4 s = *reinterpret_cast<const float4*>(p.part + i4);
+  int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  const float* part = p.part;
+  float* out = p.out;
+  int64_t n = p.n;
+  float scale = p.scale;
+  if (i4 >= n) {  // second segment
+    i4 -= n;
+    part = p.part2; out = p.out2; n = p.n2; scale = p.scale2;
+    if (i4 >= n) return;
+  }
+  float4 s = *reinterpret_cast<const float4*>(part + i4);
   for (int k = 1; k < p.splits; ++k) {
-    const float4 v = *reinterpret_cast<const float4*>(p.part + (int64_t)k * p.n + i4);
+    const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + i4);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
-  s.x *= p.scale; s.y *= p.scale; s.z *= p.scale; s.w *= p.scale;
-  *reinterpret_cast<float4*>(p.out + i4) = s;
+  s.x *= scale; s.y *= scale; s.z *= scale; s.w *= scale;
+  *reinterpret_cast<float4*>(out + i4) = s;
 }
 
 template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
@@ -317,13 +326,15 @@ hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStrea
     case GEMM_NT: return launch_tiles<true, true, bf16, false>(tile, a, s);
     case GEMM_TN_F32: return launch_tiles<false, false, float, true>(tile, a, s);
     case GEMM_NN_F32: return launch_tiles<true, false, float, false>(tile, a, s);
+    case GEMM_TT: return launch_tiles<false, true, bf16, false>(tile, a, s);
+    case GEMM_NN_F32_COLSUM: return launch_tiles<true, false, float, true>(tile, a, s);
     case GEMM_NT_F32: return launch_tiles<true, true, float, false>(tile, a, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s) {
-  const int64_t groups = (a.n / 4 + 255) / 256;
+  const int64_t groups = ((a.n + a.n2) / 4 + 255) / 256;
   if (groups <= 0) return hipSuccess;
   hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)groups), dim3(256), 0, s, a);
   return hipGetLastError();

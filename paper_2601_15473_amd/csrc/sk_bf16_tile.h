@@ -142,10 +142,11 @@ __device__ __forceinline__ bf16x8 read_frag_rowmajor(const bf16* tile, int e0, i
 }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  // round to nearest even; inputs are finite sums
-  const bf16 a = (bf16)lo, b = (bf16)hi;
-  return (uint32_t)__builtin_bit_cast(unsigned short, a) |
-         ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+  // round to nearest even, both halves in one v_cvt_pk_bf16_f32
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {

@@ -256,12 +256,14 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
 // These shapes are bound by bytes, not flops, so the kernel keeps two loads in
 // flight per thread at all times (two register sets, prefetch distance two) and is
 // small enough in LDS and registers for two work-groups per CU.
-//   - waves 2 x 2: wave (wm, wn) owns rows 32 wm.. of the token tile throughout;
-//   - stage 1 walks K1 in 64-wide chunks (x chunk + B1 chunk per step);
-//   - stage 2 takes B2 one whole [R x 64] tile at a time (no k loop inside a tile):
-//     each wave does R/16 MFMAs on two interleaved accumulators per tile.
+//   - stage 1 (waves 2 x 2) walks K1 in 64-wide chunks (x chunk + B1 chunk per step);
+//   - stage 2 takes B2 one whole [R x 128] tile at a time (no k loop inside a tile).
+//     The LDS pipe is the scarce resource here (a 64-lane LDS instruction costs the
+//     CU about 9 cycles, a transposing read twice that per fragment), so the waves
+//     split the tile's columns 1 x 4: every wave holds all 64 rows of Zt in
+//     registers and each B2 fragment is read from LDS exactly once.
 // ---------------------------------------------------------------------------
-constexpr int CS_BN = 64;
+constexpr int CS_BN = 128;
 
 template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
 struct SmallLds {
@@ -271,24 +273,27 @@ struct SmallLds {
   static constexpr int Z_LD = RT + 8;
   static constexpr int Z_BYTES = CH_BM * Z_LD * 2;
   static constexpr int OUT_LD = CS_BN * 2 + 8;
-  static constexpr int S2_BYTES = 2 * TB2::ELEMS * 2 + CH_BM * OUT_LD;
+  static constexpr int OUT_BYTES = CH_BM * OUT_LD;
+  // Zt is dead once every wave has lifted it into registers: the output staging reuses it
+  static constexpr int HEAD_BYTES = Z_BYTES > OUT_BYTES ? Z_BYTES : OUT_BYTES;
+  static constexpr int S2_BYTES = 2 * TB2::ELEMS * 2;
   static constexpr int S1_BYTES = FUSED ? 2 * (TA::ELEMS + TB1::ELEMS) * 2 : 0;
-  static constexpr int BYTES = Z_BYTES + (S1_BYTES > S2_BYTES ? S1_BYTES : S2_BYTES);
+  static constexpr int BYTES = HEAD_BYTES + (S1_BYTES > S2_BYTES ? S1_BYTES : S2_BYTES);
 };
 
 template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
-__global__ __launch_bounds__(256, 2) void chain_small_kernel(const ChainArgs p) {
+__global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   typedef SmallLds<RT, B2_KC, FUSED, B1_KC> L;
   typedef typename L::TB2 TB2;
   constexpr int KS = RT / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[L::BYTES];
   bf16* const Zs = reinterpret_cast<bf16*>(smem);
-  unsigned char* const work = smem + L::Z_BYTES;
+  unsigned char* const ostage = smem;
+  unsigned char* const work = smem + L::HEAD_BYTES;
   bf16* const Bbuf = reinterpret_cast<bf16*>(work);
-  unsigned char* const ostage = work + 2 * TB2::ELEMS * 2;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 1, wn = wave & 1;  // stage-1 wave grid
   const int wg = xcd_remap(blockIdx.x, p.tiles_m * p.n_slices);
   const int tile_m = wg / p.n_slices, slice = wg % p.n_slices;
   const int m0 = tile_m * CH_BM;
@@ -419,13 +424,15 @@ __global__ __launch_bounds__(256, 2) void chain_small_kernel(const ChainArgs p) 
   }
   __syncthreads();  // Zt complete; stage-1 buffers (aliasing Bbuf) are free
 
-  // this wave's 32 rows of Zt, as MFMA fragments, for the rest of the kernel
-  bf16x8 fa[KS];
+  // all 64 rows of Zt, as MFMA fragments, in every wave for the rest of the kernel
+  bf16x8 fa[2][KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) fa[ks] = read_frag_rowmajor<L::Z_LD>(Zs, wm * 32, ks, lane);
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fa[i][ks] = read_frag_rowmajor<L::Z_LD>(Zs, i * 32, ks, lane);
 
   TB2::store(Bbuf, rb0, tid);
-  __syncthreads();
+  __syncthreads();  // also: every wave is done reading Zt, whose space the output staging reuses
 
   bf16* __restrict__ C = static_cast<bf16*>(p.C);
   const float scale = p.scale;
@@ -439,41 +446,37 @@ __global__ __launch_bounds__(256, 2) void chain_small_kernel(const ChainArgs p) 
     const int n0 = (t_begin + jt) * CS_BN;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int cc = wn * 32 + q * 8 + (lane >> 5) * 4;
+      const int cc = wave * 32 + q * 8 + (lane >> 5) * 4;
       typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
       const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(bias_w.rsrc, (n0 + cc) * 2, 0, 0);
       bv[q] = make_uint2(v.x, v.y);
     }
   };
 
+  // one [64 x 128] output tile: wave w owns columns 32 w .. 32 w + 31 of it
   auto tile = [&](int jt, const bf16* Bs, const uint2 (&bv)[4]) {
     f32x16 a0, a1;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < KS; ks += 2) {
-      const bf16x8 f0 = read_frag<B2_KC, TB2::LD>(Bs, wn * 32, ks, lane);
-      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0, fa[ks], a0, 0, 0, 0);
-      if (ks + 1 < KS) {
-        const bf16x8 f1 = read_frag<B2_KC, TB2::LD>(Bs, wn * 32, ks + 1, lane);
-        a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, fa[ks + 1], a1, 0, 0, 0);
-      }
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 fb = read_frag<B2_KC, TB2::LD>(Bs, wave * 32, ks, lane);
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[0][ks], a0, 0, 0, 0);
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[1][ks], a1, 0, 0, 0);
     }
     const int n0 = (t_begin + jt) * CS_BN;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int cc = wn * 32 + q * 8 + (lane >> 5) * 4;
-      float v[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = (a0[q * 4 + e] + a1[q * 4 + e]) * scale;
-      v[0] += bf16_bits_to_float(bv[q].x & 0xffffu);
-      v[1] += bf16_bits_to_float(bv[q].x >> 16);
-      v[2] += bf16_bits_to_float(bv[q].y & 0xffffu);
-      v[3] += bf16_bits_to_float(bv[q].y >> 16);
+      const int cc = wave * 32 + q * 8 + (lane >> 5) * 4;
+      const float b0 = bf16_bits_to_float(bv[q].x & 0xffffu), b1 = bf16_bits_to_float(bv[q].x >> 16);
+      const float b2 = bf16_bits_to_float(bv[q].y & 0xffffu), b3 = bf16_bits_to_float(bv[q].y >> 16);
       uint2 w;
-      w.x = pack_bf16x2(v[0], v[1]);
-      w.y = pack_bf16x2(v[2], v[3]);
-      *reinterpret_cast<uint2*>(ostage + (wm * 32 + (lane & 31)) * L::OUT_LD + cc * 2) = w;
+      w.x = pack_bf16x2(a0[q * 4 + 0] * scale + b0, a0[q * 4 + 1] * scale + b1);
+      w.y = pack_bf16x2(a0[q * 4 + 2] * scale + b2, a0[q * 4 + 3] * scale + b3);
+      *reinterpret_cast<uint2*>(ostage + (lane & 31) * L::OUT_LD + cc * 2) = w;
+      w.x = pack_bf16x2(a1[q * 4 + 0] * scale + b0, a1[q * 4 + 1] * scale + b1);
+      w.y = pack_bf16x2(a1[q * 4 + 2] * scale + b2, a1[q * 4 + 3] * scale + b3);
+      *reinterpret_cast<uint2*>(ostage + (32 + (lane & 31)) * L::OUT_LD + cc * 2) = w;
     }
     __syncthreads();
     constexpr int PPR = CS_BN / 8;  // 16-byte pieces per output row

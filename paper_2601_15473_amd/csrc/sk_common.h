@@ -30,19 +30,26 @@ struct GemmArgs {
   float* colsum;       // [splits, N] fp32 sums of B over k, or null (EPI_PARTIAL only)
   int64_t lda, ldb, ldc;
   int M, N, K;
+  int n_store;         // columns written per row: N, or up to ldc to zero-fill row padding
+                       // (columns >= N of the product are exact zeros); 0 means N
   int k_per_split;     // multiple of the kernel's k chunk; K when not split
   int splits;
   int tiles_m, tiles_n;
   float scale;
 };
 
-// out[i] = scale * sum_s part[s][i] for i < n, in split order (deterministic).
+// Sum of split-K slabs in split order (deterministic), two outputs in one launch:
+//   out[i]  = scale  * sum_s part[s][i]   for i < n      (slabs n elements apart)
+//   out2[j] = scale2 * sum_s part2[s][j]  for j < n2     (slabs n2 elements apart; n2 may be 0)
 struct ReduceArgs {
   const float* part;
   float* out;
-  int64_t n;           // elements per slab
+  int64_t n;
+  const float* part2;
+  float* out2;
+  int64_t n2;
   int splits;
-  float scale;
+  float scale, scale2;
 };
 
 // XCD-aware work-group order.  Work-groups are handed to the 8 XCDs round-robin,

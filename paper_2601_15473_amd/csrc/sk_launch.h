@@ -10,6 +10,8 @@ enum GemmKind : int {
   GEMM_TN_F32 = 2,  // A [K,M], B [K,N], split-K   -> fp32 (+ column sums of B)
   GEMM_NN_F32 = 3,  // as GEMM_NN, split-K          -> fp32 slabs
   GEMM_NT_F32 = 4,  // as GEMM_NT, split-K          -> fp32 slabs
+  GEMM_TT = 5,      // A [K,M], B [N,K]            -> storage type
+  GEMM_NN_F32_COLSUM = 6,  // as GEMM_NN_F32, plus the column sums of B
 };
 
 enum TileCfg : int {
