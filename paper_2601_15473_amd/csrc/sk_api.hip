@@ -49,19 +49,26 @@ sk_status check_shape(int64_t tokens, int64_t in, int64_t out, int32_t l, int32_
   return SK_OK;
 }
 
-// Largest tile that still gives every CU a work-group, without tiles that are
-// mostly padding; the smallest fitting tile when the problem cannot fill the chip.
-int choose_tile(int64_t M, int64_t N, int splits) {
+// Tile choice for the general GEMM (measured on MI355X).  The 256 x 256 tile with eight
+// waves has the best steady state but a long prologue and epilogue, so it only pays
+// with a long contraction; 128 x 128 runs two work-groups per CU, which overlaps one
+// tile's stores with the other's MFMAs.  Otherwise: the largest tile that still gives
+// every CU a work-group without being mostly padding, the smallest when the problem
+// cannot fill the chip.
+int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
+  if (const char* e = getenv("SK_TUNE_TILE")) return atoi(e);  // tuning experiments only
   const int64_t m_cap = (M + 63) / 64 * 64, n_cap = (N + 63) / 64 * 64;
-  int best = TILE_64x64;
-  for (int t = 0; t < TILE_COUNT; ++t) {
+  static const int order[] = {TILE_256x256_W8, TILE_128x128, TILE_128x64, TILE_64x128, TILE_64x64};
+  for (int i = 0; i < (int)(sizeof(order) / sizeof(order[0])); ++i) {
+    const int t = order[i];
     int bm, bn;
     tile_dims(t, bm, bn);
     if (bm > m_cap || bn > n_cap) continue;
+    if (t == TILE_256x256_W8 && K / splits < 2048) continue;
     const int64_t wgs = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * splits;
     if (wgs >= NUM_CUS) return t;
   }
-  return best;
+  return TILE_64x64;
 }
 
 struct WeightPlan {
@@ -69,6 +76,7 @@ struct WeightPlan {
   int splits;
   int k_per_split;
   int64_t ldz;         // bf16: row stride of Z^T [R, ldz]
+  bool own_colsum;     // db from its own kernel (the big tile has no registers for it)
   size_t z_bytes, part_bytes, csum_bytes;
   size_t total() const { return z_bytes + part_bytes + csum_bytes; }
 };
@@ -81,7 +89,14 @@ WeightPlan plan_weight(const Shape& s) {
   int bm, bn;
   if (s.dtype == SK_BF16) {
     w.tile = s.R > 64 ? TILE_128x64 : TILE_64x64;
-    if (((s.R + 127) / 128) * ((s.out + 127) / 128) >= NUM_CUS) w.tile = TILE_128x128;
+    if (((s.R + 255) / 256) * ((s.out + 255) / 256) >= NUM_CUS) {
+      w.tile = TILE_256x256_W8;
+      w.own_colsum = true;
+    } else if (((s.R + 127) / 128) * ((s.out + 127) / 128) >= NUM_CUS) w.tile = TILE_128x128;
+    if (const char* e = getenv("SK_TUNE_WTILE")) {  // tuning experiments only
+      w.tile = atoi(e);
+      w.own_colsum = w.tile == TILE_256x256_W8 || w.tile == TILE_256x256;
+    }
     tile_dims(w.tile, bm, bn);
     w.ldz = (s.T + 63) / 64 * 64;
     w.z_bytes = align_up((size_t)s.R * w.ldz * 2);
@@ -194,7 +209,7 @@ size_t workspace_for(sk_op op, const Shape& s) {
 }
 
 hipError_t gemm(const Shape& s, GemmKind kind, GemmArgs a, hipStream_t st) {
-  if (s.dtype == SK_BF16) return launch_gemm_bf16(kind, choose_tile(a.M, a.N, 1), a, st);
+  if (s.dtype == SK_BF16) return launch_gemm_bf16(kind, choose_tile(a.M, a.N, a.K, 1), a, st);
   return launch_gemm_f32(kind, a, st);
 }
 
@@ -276,7 +291,8 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
     return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_fwd (expand)");
   }
   // Z = x . S_cat, then y = scale * Z . U_cat + bias
-  hipError_t e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+  hipError_t e;
+  e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (x.S)");
   e = gemm(s, GEMM_NN, dense_args(workspace, s.R, U_cat, out, y, out, tokens, out, s.R, scale, bias), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (Z.U)");
@@ -338,7 +354,7 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
   const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
   if (st != SK_OK) return st;
   const WeightPlan w = plan_weight(s);
-  if (!workspace || workspace_bytes < w.total()) return SK_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < workspace_for(SK_OP_BWD_WEIGHT, s)) return SK_ERR_WORKSPACE;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const float scale = 1.0f / (float)l;
   g_hip_error.clear();
@@ -356,7 +372,7 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
   if (s.dtype == SK_BF16) {
     GemmArgs z = dense_args(S_cat, s.R, x, in, Z, w.ldz, s.R, tokens, in, 1.0f, nullptr);
     z.n_store = (int)w.ldz;
-    e = launch_gemm_bf16(GEMM_TT, choose_tile(s.R, tokens, 1), z, hs);
+    e = launch_gemm_bf16(GEMM_TT, choose_tile(s.R, tokens, in, 1), z, hs);
     a.A = Z; a.lda = w.ldz;
   } else {
     e = launch_gemm_f32(GEMM_NN, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
@@ -374,8 +390,16 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
   } else {
     a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
   }
-  e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs)
-                         : launch_gemm_f32(GEMM_TN_F32, a, hs);
+  if (s.dtype == SK_BF16 && w.own_colsum) {
+    a.colsum = nullptr;
+    e = launch_gemm_bf16(GEMM_NN_F32, w.tile, a, hs);
+    if (e == hipSuccess && dbias)
+      e = launch_colsum_bf16(dY, w.splits == 1 ? dbias : cpart, (int)tokens, (int)out, w.splits,
+                             w.k_per_split, hs);
+  } else {
+    e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs)
+                           : launch_gemm_f32(GEMM_TN_F32, a, hs);
+  }
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (Z^T.dY)");
   if (w.splits > 1) {
     ReduceArgs r{};

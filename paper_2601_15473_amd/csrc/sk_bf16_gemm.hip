@@ -36,21 +36,23 @@ template <typename OutT> struct OutTraits;
 template <> struct OutTraits<bf16> { static constexpr int PIECE = 8; };    // 4 bf16
 template <> struct OutTraits<float> { static constexpr int PIECE = 16; };  // 4 fp32
 
-template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM, int PF>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
-  typedef OpTile<BM, A_KC> TA;
-  typedef OpTile<BN, B_KC> TB;
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
+          bool COLSUM, int PF>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const GemmArgs p) {
+  constexpr int NTH = 64 * WAVES_M * WAVES_N;
+  typedef OpTile<BM, A_KC, BK, NTH> TA;
+  typedef OpTile<BN, B_KC, BK, NTH> TB;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int STAGE = TA::ELEMS + TB::ELEMS;
   constexpr int PIECE = OutTraits<OutT>::PIECE;
   constexpr int EP_LD = WN * (int)sizeof(OutT) + PIECE;  // bytes per staged output row
-  constexpr int EP_BYTES = 4 * 32 * EP_LD;
+  constexpr int EP_BYTES = WAVES_M * WAVES_N * 32 * EP_LD;
   constexpr int LDS_BYTES = (2 * STAGE * 2 > EP_BYTES) ? 2 * STAGE * 2 : EP_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
   bf16* const lds = reinterpret_cast<bf16*>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   const int tiles = p.tiles_m * p.tiles_n;
   const int id = xcd_remap(blockIdx.x, tiles * p.splits);
@@ -135,16 +137,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs p) {
       const int k0 = k_begin + (kc + 1) * BK;
       read(As, 0, fa0, fb0);
       __builtin_amdgcn_sched_barrier(0);
-      // k step 0: MFMAs + fragment reads of step 1 + the A loads of the next chunk
+      // k step 0: MFMAs + fragment reads of step 1 + all loads of the next chunk (issued
+      // as early as possible: they are stored to LDS three k steps later)
       read(As, 1, fa1, fb1);
       TA::load(ra, A, p.lda, m0, p.M, k0, k_end, p.K, tid);
-      mma(fa0, fb0);
-      sched_phase<NMMA, NDSR, TA::PIECES, 0>();
-      // k step 1: + the B loads of the next chunk
-      read(As, 2, fa0, fb0);
       TB::load(rb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
+      mma(fa0, fb0);
+      sched_phase<NMMA, NDSR, NVM, 0>();
+      // k step 1
+      read(As, 2, fa0, fb0);
       mma(fa1, fb1);
-      sched_phase<NMMA, NDSR, TB::PIECES, 0>();
+      sched_phase<NMMA, NDSR, 0, 0>();
       // k step 2
       read(As, 3, fa1, fb1);
       mma(fa0, fb0);
@@ -295,27 +298,30 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const ReduceArgs p) 
   *reinterpret_cast<float4*>(out + i4) = s;
 }
 
-template <int BM, int BN, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
 static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   a.tiles_m = (a.M + BM - 1) / BM;
   a.tiles_n = (a.N + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  // big tiles have no registers to spare for a second set of loads in flight
-  constexpr int PF = (BM * BN >= 256 * 256) ? 1 : 2;
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, A_KC, B_KC, OutT, COLSUM, PF>),
-                     dim3((unsigned)grid), dim3(256), 0, s, a);
+  // big per-wave tiles have no registers to spare for a second set of loads in flight
+  constexpr int PF = (BM * BN / (WAVES_M * WAVES_N) >= 128 * 64) ? 1 : 2;
+  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>),
+                     dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), 0, s, a);
   return hipGetLastError();
 }
 
 template <bool A_KC, bool B_KC, typename OutT, bool COLSUM>
 static hipError_t launch_tiles(int tile, const GemmArgs& a, hipStream_t s) {
   switch (tile) {
-    case TILE_256x256: return launch_cfg<256, 256, A_KC, B_KC, OutT, COLSUM>(a, s);
-    case TILE_128x128: return launch_cfg<128, 128, A_KC, B_KC, OutT, COLSUM>(a, s);
-    case TILE_128x64: return launch_cfg<128, 64, A_KC, B_KC, OutT, COLSUM>(a, s);
-    case TILE_64x128: return launch_cfg<64, 128, A_KC, B_KC, OutT, COLSUM>(a, s);
-    case TILE_64x64: return launch_cfg<64, 64, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_256x256: return launch_cfg<256, 256, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_128x128: return launch_cfg<128, 128, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_128x64: return launch_cfg<128, 64, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_64x128: return launch_cfg<64, 128, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_64x64: return launch_cfg<64, 64, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_256x128: return launch_cfg<256, 128, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_128x256: return launch_cfg<128, 256, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_256x256_W8: return launch_cfg<256, 256, 2, 4, A_KC, B_KC, OutT, COLSUM>(a, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -331,6 +337,49 @@ hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStrea
     case GEMM_NT_F32: return launch_tiles<true, true, float, false>(tile, a, s);
     default: return hipErrorInvalidValue;
   }
+}
+
+// Column sums of a dense row-major bf16 matrix [rows, cols] in fp32, the row range cut
+// into `splits` runs of rows_per_split (out[s][c] = sum of rows of run s; fixed order).
+// One work-group owns 64 columns of one run: 8 lanes cover them 16 bytes each, 32
+// lanes-groups stride over the rows, then the 32 partial sums meet in LDS.
+__global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* __restrict__ in,
+                                                          float* __restrict__ out, int rows,
+                                                          int cols, int rows_per_split) {
+  __shared__ float part[32][65];
+  const int tid = threadIdx.x, cg = tid & 7, rl = tid >> 3;
+  const int c = blockIdx.x * 64 + cg * 8;
+  const int r_begin = blockIdx.y * rows_per_split;
+  const int r_end = (r_begin + rows_per_split < rows) ? r_begin + rows_per_split : rows;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c < cols) {
+#pragma unroll 4
+    for (int r = r_begin + rl; r < r_end; r += 32) {
+      const uint4 v = *reinterpret_cast<const uint4*>(in + (int64_t)r * cols + c);
+      const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] += __builtin_bit_cast(float, w[e] << 16);
+        acc[2 * e + 1] += __builtin_bit_cast(float, w[e] & 0xffff0000u);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[rl][cg * 8 + e] = acc[e];
+  __syncthreads();
+  if (tid < 64 && blockIdx.x * 64 + tid < cols) {
+    float s = 0.f;
+    for (int i = 0; i < 32; ++i) s += part[i][tid];
+    out[(int64_t)blockIdx.y * cols + blockIdx.x * 64 + tid] = s;
+  }
+}
+
+hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,
+                              int rows_per_split, hipStream_t s) {
+  const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)splits);
+  hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(256), 0, s,
+                     static_cast<const unsigned short*>(in), out, rows, cols, rows_per_split);
+  return hipGetLastError();
 }
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s) {

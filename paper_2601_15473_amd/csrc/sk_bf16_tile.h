@@ -44,7 +44,8 @@ __device__ __forceinline__ uint4 window_load16(const GWindow& w, unsigned byte_o
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// One operand tile of EXT rows (m or n extent) by KX (k extent, default BK) in LDS.
+// One operand tile of EXT rows (m or n extent) by KX (k extent, default BK) in LDS,
+// moved by a work-group of NTH threads.
 //   KC  = true : source is [EXT, K] with k contiguous; stored [EXT][KX] without padding,
 //                the 16-byte pieces of each row XOR-swizzled by the row number
 //                (kc_piece): a store instruction then fills whole 256-byte bank rows
@@ -65,12 +66,12 @@ __device__ __forceinline__ int kc_piece(int row, int pc) {
   return pc ^ ((row / ROWS_PER_BANKROW) & (PPR - 1));
 }
 
-template <int EXT, bool KC, int KX = BK>
+template <int EXT, bool KC, int KX = BK, int NTH = 256>
 struct OpTile {
   static constexpr int LD = KC ? KX : EXT + 32;
   static constexpr int ELEMS = KC ? EXT * KX : KX * (EXT + 32);
-  static constexpr int PIECES = EXT * KX / 2048;  // 16-byte pieces per thread (256 threads)
-  static_assert(EXT * KX % 2048 == 0, "tile must split evenly over 256 threads");
+  static constexpr int PIECES = EXT * KX / (8 * NTH);  // 16-byte pieces per thread (NTH threads)
+  static_assert(EXT * KX % (8 * NTH) == 0, "tile must split evenly over the work-group");
 
   // Global -> registers, branch free.  `g` is the whole array ([ext_total, k_total]
   // for KC, [k_total, ext_total] otherwise, row stride ld).  The tile starts at
@@ -86,7 +87,7 @@ struct OpTile {
     const unsigned ldb = (unsigned)ld * 2u;
 #pragma unroll
     for (int p = 0; p < PIECES; ++p) {
-      const int piece = p * 256 + tid;
+      const int piece = p * NTH + tid;
       constexpr int PPR = KC ? KX / 8 : EXT / 8;
       const int row = piece / PPR, col = (piece % PPR) * 8;
       // rows past the end of the array fall outside the window by themselves
@@ -100,7 +101,7 @@ struct OpTile {
   static __device__ __forceinline__ void store(bf16* tile, const uint4 (&r)[PIECES], int tid) {
 #pragma unroll
     for (int p = 0; p < PIECES; ++p) {
-      const int piece = p * 256 + tid;
+      const int piece = p * NTH + tid;
       constexpr int PPR = KC ? KX / 8 : EXT / 8;
       const int row = piece / PPR;
       const int pc = KC ? kc_piece<KX>(row, piece % PPR) : piece % PPR;

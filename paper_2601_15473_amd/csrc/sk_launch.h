@@ -20,11 +20,15 @@ enum TileCfg : int {
   TILE_128x64 = 2,
   TILE_64x128 = 3,
   TILE_64x64 = 4,
-  TILE_COUNT = 5,
+  TILE_256x128 = 5,
+  TILE_128x256 = 6,
+  TILE_256x256_W8 = 7,   // 256 x 256 with eight waves (2 x 4), two per SIMD
+  TILE_COUNT = 8,
 };
 
 inline void tile_dims(int tile, int& bm, int& bn) {
-  static const int dims[TILE_COUNT][2] = {{256, 256}, {128, 128}, {128, 64}, {64, 128}, {64, 64}};
+  static const int dims[TILE_COUNT][2] = {{256, 256}, {128, 128}, {128, 64}, {64, 128},
+                                          {64, 64},   {256, 128}, {128, 256}, {256, 256}};
   bm = dims[tile][0];
   bn = dims[tile][1];
 }
@@ -36,6 +40,10 @@ hipError_t launch_gemm_f32(GemmKind kind, const GemmArgs& a, hipStream_t s);
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16;
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s);
+// fp32 column sums of the dense row-major bf16 matrix in [rows, cols], one output row of
+// `cols` sums per run of rows_per_split rows (splits runs)
+hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,
+                              int rows_per_split, hipStream_t s);
 
 // Second contraction of the layer with the R-wide intermediate of a 64-token tile
 // resident on chip (bf16, R <= 512), optionally with the first contraction fused in:

@@ -127,6 +127,16 @@ def test_parity_llm_mlp_full_size_sampled(sk):
     assert torch.isfinite(dev.dU).all() and torch.isfinite(dev.db).all()
 
 
+def test_forced_big_tiles(sk, monkeypatch):
+    """The large-shape code paths (big tiles, the bias gradient from its own kernel)
+    on a shape small enough for a full oracle pass."""
+    w = W.Workload("bf16_forced_paths", 700, 320, 592, 2, 72, "bf16", seed=10)
+    for tile, wtile in ((7, 7), (0, 5), (5, 1), (6, 2)):
+        monkeypatch.setenv("SK_TUNE_TILE", str(tile))
+        monkeypatch.setenv("SK_TUNE_WTILE", str(wtile))
+        check_all(sk, w, 2)
+
+
 def test_bit_reproducible(sk):
     """The token reduction of dU/db runs in a fixed order: two runs agree bit for bit."""
     sk.sk_set_plan(0)
