@@ -22,6 +22,24 @@ import time
 
 import numpy as np
 
+# HBM bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs of
+# this script with --calibrate-copy), summed over the call's kernels and scaled by the
+# same counters' reading for the 256 MiB calibration copy (FETCH_SIZE reads half the
+# copied bytes on this machine, factor 2.0; WRITE_SIZE reads them exactly, factor 1.0).
+# Source: profiles/c1_bert_base_ffn_up_hbm_traffic.txt.  Automatic plan only.
+MEASURED_TRAFFIC_BYTES = {
+    ("c1_bert_base_ffn_up", "fwd"): 39.6e6,
+    ("c1_bert_base_ffn_up", "bwd_input"): 51.6e6,
+    ("c1_bert_base_ffn_up", "bwd_weight"): 54.2e6,
+}
+# Kernels behind each entry point in the automatic plan for narrow sketches (R <= 128).
+CALL_KERNELS = {
+    "fwd": ["chain_small_kernel (fused)"],
+    "bwd_input": ["gemm_bf16_kernel (split-K, NT)", "chain_small_kernel (expand)"],
+    "bwd_weight": ["gemm_bf16_kernel (Z^T)", "gemm_bf16_kernel (split-K, column sums)",
+                   "reduce_splits_kernel"],
+}
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
 MFMA_F32_PEAK_TFLOPS = 157.3
@@ -55,6 +73,8 @@ def main():
     ap.add_argument("--no-dense-context", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 256 MiB device-to-device copy (for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -141,9 +161,12 @@ def main():
         achieved, peak, unit = b_dom / per_op[dom]["ms"] / 1e6, HBM_PEAK_GBS, "GB/s"
     else:
         achieved, peak, unit = f_dom / per_op[dom]["ms"] / 1e9, peak_tf, "TFLOP/s"
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom)) if args.plan == 0 and not args.tokens else None
     roofline = {
-        "bound": bound, "kernel": f"sk_linear_{dom}", "achieved": achieved, "peak": peak,
-        "unit": unit, "frac": achieved / peak, "traffic": None,
+        "bound": bound, "kernel": f"sk_linear_{dom}", "launch": "one call of the entry point",
+        "kernels_in_call": CALL_KERNELS[dom] if w.R <= 128 and w.dtype == "bf16" else None,
+        "achieved": achieved, "peak": peak,
+        "unit": unit, "frac": achieved / peak, "traffic": traffic,
         "step_frac": max(t_mfma, t_hbm) / (ms_step * 1e-3),
         "algorithmic_bytes": b_dom, "algorithmic_flops": f_dom, "ms": per_op[dom]["ms"],
     }
@@ -165,6 +188,14 @@ def main():
         "per_call": per_op,
         "roofline": roofline,
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibrate_copy_bytes"] = 256 << 20
 
     if not args.no_dense_context:
         # the dense layer the sketch replaces (hipBLASLt through torch.matmul): context only
