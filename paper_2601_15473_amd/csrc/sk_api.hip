@@ -77,6 +77,8 @@ struct WeightPlan {
   int k_per_split;
   int64_t ldz;         // bf16: row stride of Z^T [R, ldz]
   bool own_colsum;     // db from its own kernel (the big tile has no registers for it)
+  int colsum_splits;   // rows of column-sum partials: `splits`, or the own kernel's row runs
+  int colsum_rows;     // tokens per row run of the own kernel
   size_t z_bytes, part_bytes, csum_bytes;
   size_t total() const { return z_bytes + part_bytes + csum_bytes; }
 };
@@ -107,18 +109,50 @@ WeightPlan plan_weight(const Shape& s) {
     w.z_bytes = align_up((size_t)s.T * s.R * 4);
   }
   const int64_t tiles = ((s.R + bm - 1) / bm) * ((s.out + bn - 1) / bn);
-  int64_t splits = NUM_CUS / tiles;   // one wave of work-groups: no half-empty second round
-  const int64_t max_splits = (s.T + 255) / 256;
-  if (splits > max_splits) splits = max_splits;
-  if (splits > 32) splits = 32;
-  if (splits < 1) splits = 1;
-  int64_t kps = (s.T + splits - 1) / splits;
-  kps = (kps + 63) / 64 * 64;
-  splits = (s.T + kps - 1) / kps;
+  // Pick the split count with the least modelled time: rounds of work-groups over the
+  // chip x tokens per split x the tile's time per token, plus writing and re-reading one
+  // fp32 slab per split.  Rates are measured ones (flop/s one work-group sustains; HBM
+  // bytes/s); the model only has to rank the candidates.
+  const double wg_rate = s.dtype != SK_BF16 ? 0.3e12 : bm * bn >= 256 * 256 ? 5.0e12 : bm * bn >= 128 * 128 ? 3.5e12
+                         : bm * bn >= 128 * 64 ? 2.2e12 : 1.5e12;
+  const double t_token = 2.0 * bm * bn / wg_rate;
+  const double t_slab = (double)s.R * s.out * 8.0 / 4.0e12;
+  int64_t max_splits = (s.T + 255) / 256;   // at least 256 tokens each
+  if (max_splits > 32) max_splits = 32;
+  int64_t splits = 1, kps = (s.T + 63) / 64 * 64;
+  double best = -1.0;
+  for (int64_t sp = 1; sp <= max_splits; ++sp) {
+    int64_t k = (s.T + sp - 1) / sp;
+    k = (k + 63) / 64 * 64;
+    const int64_t sp_eff = (s.T + k - 1) / k;
+    const int64_t rounds = (tiles * sp_eff + NUM_CUS - 1) / NUM_CUS;
+    const double t = rounds * k * t_token + (sp_eff > 1 ? sp_eff * t_slab + 2.0e-6 : 0.0);
+    if (best < 0.0 || t < best) { best = t; splits = sp_eff; kps = k; }
+  }
+  if (const char* e = getenv("SK_TUNE_WSPLITS")) {  // tuning experiments only
+    splits = atoi(e);
+    kps = ((s.T + splits - 1) / splits + 63) / 64 * 64;
+    splits = (s.T + kps - 1) / kps;
+  }
   w.splits = (int)splits;
   w.k_per_split = (int)kps;
+  w.colsum_splits = w.splits;
+  w.colsum_rows = w.k_per_split;
+  if (w.own_colsum) {
+    // the column-sum kernel splits the tokens by itself, enough to fill the chip
+    const int64_t col_groups = (s.out + 511) / 512;
+    int64_t cs = (4 * NUM_CUS + col_groups - 1) / col_groups;
+    const int64_t max_cs = (s.T + 127) / 128;
+    if (cs > max_cs) cs = max_cs;
+    if (cs > 48) cs = 48;
+    if (cs < 1) cs = 1;
+    int64_t rows = (s.T + cs - 1) / cs;
+    rows = (rows + 31) / 32 * 32;
+    w.colsum_rows = (int)rows;
+    w.colsum_splits = (int)((s.T + rows - 1) / rows);
+  }
   w.part_bytes = splits > 1 ? align_up((size_t)splits * s.R * s.out * 4) : 0;
-  w.csum_bytes = splits > 1 ? align_up((size_t)splits * s.out * 4) : 0;
+  w.csum_bytes = w.colsum_splits > 1 ? align_up((size_t)w.colsum_splits * s.out * 4) : 0;
   return w;
 }
 
@@ -391,21 +425,24 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
     a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
   }
   if (s.dtype == SK_BF16 && w.own_colsum) {
-    a.colsum = nullptr;
+    if (dbias) {
+      e = launch_colsum_bf16(dY, w.colsum_splits == 1 ? dbias : cpart, (int)tokens, (int)out,
+                             w.colsum_splits, w.colsum_rows, hs);
+      if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (column sums)");
+    }
     e = launch_gemm_bf16(GEMM_NN_F32, w.tile, a, hs);
-    if (e == hipSuccess && dbias)
-      e = launch_colsum_bf16(dY, w.splits == 1 ? dbias : cpart, (int)tokens, (int)out, w.splits,
-                             w.k_per_split, hs);
   } else {
     e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs)
                            : launch_gemm_f32(GEMM_TN_F32, a, hs);
   }
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (Z^T.dY)");
-  if (w.splits > 1) {
+  const bool sum_dU = w.splits > 1;
+  const bool sum_db = dbias && w.colsum_splits > 1;
+  if (sum_dU || sum_db) {
     ReduceArgs r{};
-    r.part = part; r.out = dU_cat; r.n = (int64_t)s.R * out; r.scale = scale;
-    r.part2 = cpart; r.out2 = dbias; r.n2 = dbias ? out : 0; r.scale2 = 1.0f;
-    r.splits = w.splits;
+    r.part = part; r.out = dU_cat; r.n = sum_dU ? (int64_t)s.R * out : 0; r.scale = scale;
+    r.part2 = cpart; r.out2 = dbias; r.n2 = sum_db ? out : 0; r.scale2 = 1.0f;
+    r.splits = w.splits; r.splits2 = w.colsum_splits;
     e = launch_reduce_splits(r, hs);
     if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (sum of splits)");
   }

@@ -162,7 +162,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
   } else {
     // Small tiles: an iteration is too short to cover a load's latency, so two
     // register sets keep the loads of chunk kc + 2 in flight while chunk kc + 1,
-    // loaded one iteration earlier, is stored.
+    // loaded one iteration earlier, is stored.  (Four and six sets were measured on the
+    // shapes of this layer and were no faster.)
     uint4 ra0[TA::PIECES], rb0[TB::PIECES], ra1[TA::PIECES], rb1[TB::PIECES];
     TA::load(ra0, A, p.lda, m0, p.M, k_begin, k_end, p.K, tid);
     TB::load(rb0, B, p.ldb, n0, p.N, k_begin, k_end, p.K, tid);
@@ -275,6 +276,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
         }
     }
   }
+
 }
 
 // Sums the split-K slabs in index order; see ReduceArgs.
@@ -284,13 +286,15 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const ReduceArgs p) 
   float* out = p.out;
   int64_t n = p.n;
   float scale = p.scale;
+  int splits = p.splits;
   if (i4 >= n) {  // second segment
     i4 -= n;
-    part = p.part2; out = p.out2; n = p.n2; scale = p.scale2;
+    part = p.part2; out = p.out2; n = p.n2; scale = p.scale2; splits = p.splits2;
     if (i4 >= n) return;
   }
   float4 s = *reinterpret_cast<const float4*>(part + i4);
-  for (int k = 1; k < p.splits; ++k) {
+#pragma unroll 8
+  for (int k = 1; k < splits; ++k) {
     const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + i4);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
@@ -341,20 +345,22 @@ hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStrea
 
 // Column sums of a dense row-major bf16 matrix [rows, cols] in fp32, the row range cut
 // into `splits` runs of rows_per_split (out[s][c] = sum of rows of run s; fixed order).
-// One work-group owns 64 columns of one run: 8 lanes cover them 16 bytes each, 32
-// lanes-groups stride over the rows, then the 32 partial sums meet in LDS.
+// One work-group owns 512 columns of one run: a wave reads one whole 1 KB row segment
+// per instruction (lane = 8 columns), the four waves stride over the rows, and their
+// four partial sums meet in LDS and are added in wave order.
+constexpr int COLSUM_COLS = 512;
 __global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* __restrict__ in,
                                                           float* __restrict__ out, int rows,
                                                           int cols, int rows_per_split) {
-  __shared__ float part[32][65];
-  const int tid = threadIdx.x, cg = tid & 7, rl = tid >> 3;
-  const int c = blockIdx.x * 64 + cg * 8;
+  __shared__ float part[4][COLSUM_COLS + 8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = blockIdx.x * COLSUM_COLS + lane * 8;
   const int r_begin = blockIdx.y * rows_per_split;
   const int r_end = (r_begin + rows_per_split < rows) ? r_begin + rows_per_split : rows;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (c < cols) {
-#pragma unroll 4
-    for (int r = r_begin + rl; r < r_end; r += 32) {
+#pragma unroll 8
+    for (int r = r_begin + wave; r < r_end; r += 4) {
       const uint4 v = *reinterpret_cast<const uint4*>(in + (int64_t)r * cols + c);
       const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -365,18 +371,18 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* 
     }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) part[rl][cg * 8 + e] = acc[e];
+  for (int e = 0; e < 8; ++e) part[wave][lane * 8 + e] = acc[e];
   __syncthreads();
-  if (tid < 64 && blockIdx.x * 64 + tid < cols) {
-    float s = 0.f;
-    for (int i = 0; i < 32; ++i) s += part[i][tid];
-    out[(int64_t)blockIdx.y * cols + blockIdx.x * 64 + tid] = s;
+  for (int i = tid; i < COLSUM_COLS; i += 256) {
+    const int gc = blockIdx.x * COLSUM_COLS + i;
+    if (gc < cols)
+      out[(int64_t)blockIdx.y * cols + gc] = ((part[0][i] + part[1][i]) + part[2][i]) + part[3][i];
   }
 }
 
 hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,
                               int rows_per_split, hipStream_t s) {
-  const dim3 grid((unsigned)((cols + 63) / 64), (unsigned)splits);
+  const dim3 grid((unsigned)((cols + COLSUM_COLS - 1) / COLSUM_COLS), (unsigned)splits);
   hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(256), 0, s,
                      static_cast<const unsigned short*>(in), out, rows, cols, rows_per_split);
   return hipGetLastError();

@@ -40,7 +40,7 @@ struct GemmArgs {
 
 // Sum of split-K slabs in split order (deterministic), two outputs in one launch:
 //   out[i]  = scale  * sum_s part[s][i]   for i < n      (slabs n elements apart)
-//   out2[j] = scale2 * sum_s part2[s][j]  for j < n2     (slabs n2 elements apart; n2 may be 0)
+//   out2[j] = scale2 * sum_s part2[s][j]  for j < n2     (splits2 slabs n2 elements apart; n2 may be 0)
 struct ReduceArgs {
   const float* part;
   float* out;
@@ -48,7 +48,7 @@ struct ReduceArgs {
   const float* part2;
   float* out2;
   int64_t n2;
-  int splits;
+  int splits, splits2;
   float scale, scale2;
 };
 
