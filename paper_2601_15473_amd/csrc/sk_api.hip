@@ -177,10 +177,14 @@ Plan pick_plan(const Shape& s, sk_op op) {
   }
   // automatic (measured on MI355X): the on-chip plans win while the sketch is narrow
   // (R <= 128: the layer is bound by bytes and by launch count); wider sketches run
-  // faster as two general GEMMs with large tiles.  Forward fuses (its first
-  // contraction is short, so recomputing it per N slice is cheap); the input gradient's
-  // first contraction runs over `out`, too long to recompute, so it is split instead.
-  if (chain_ok && s.R <= 128) return op == SK_OP_FWD ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
+  // faster as two general GEMMs with large tiles.  One fused kernel recomputes the first
+  // contraction once per N slice, which is cheap while that contraction is short (up to
+  // about 1500 long: the forward of an up-projection, either call of a square layer);
+  // a long one (the input gradient of an up-projection runs over `out`) is split instead.
+  if (chain_ok && s.R <= 128) {
+    const int64_t k1 = op == SK_OP_FWD ? s.in : s.out;
+    return k1 <= 1536 ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
+  }
   return PLAN_TWO_GEMM;
 }
 

@@ -396,29 +396,53 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
       *reinterpret_cast<uint4*>(Zs + r * L::Z_LD + c) = v;
     }
   } else {
-    // sum of fp32 split-K slabs in index order, rounded once to bf16; all loads of a
-    // piece are issued before the first add
+    // Sum of the fp32 split-K slabs in index order, rounded once to bf16.  The loads
+    // are branch free (buffer windows, one per slab; a masked lane reads zero) and go
+    // out four slabs x all pieces of the thread at a time, so the whole tile costs one
+    // or two trips to memory instead of one per piece.
     const float* __restrict__ Zp = static_cast<const float*>(p.Z);
     constexpr int PPR = RT / 4;
-    constexpr int MAXS = 8;
+    constexpr int NP = (CH_BM * PPR) / 256;  // pieces of four floats per thread
+    constexpr int MAXS = 8, GROUP = 4;
+    unsigned off[NP];
 #pragma unroll
-    for (int i = 0; i < (CH_BM * PPR) / 256; ++i) {
+    for (int i = 0; i < NP; ++i) {
       const int piece = i * 256 + tid;
       const int r = piece / PPR, c = (piece % PPR) * 4;
-      float4 v[MAXS];
-      const bool ok = m0 + r < p.M && c < p.R;
-      const float* src = Zp + (int64_t)(m0 + r) * p.R + c;
+      off[i] = c < p.R ? (unsigned)(r * p.R + c) * 4u : OOB_OFFSET;  // rows past M fall outside
+    }
+    float4 sum[NP];
 #pragma unroll
-      for (int k = 0; k < MAXS; ++k) {
-        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ok && k < p.z_splits) v[k] = *reinterpret_cast<const float4*>(src + (int64_t)k * p.z_slab);
+    for (int g = 0; g < MAXS / GROUP; ++g) {
+      if (g * GROUP < p.z_splits) {  // uniform
+        f32x4 v[GROUP][NP];
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) {
+          const int sp = g * GROUP + k;
+          // slabs past z_splits: an empty window, every lane reads zero
+          const int64_t origin = (int64_t)sp * p.z_slab + (int64_t)m0 * p.R;
+          const GWindow w = make_window(Zp, origin, sp < p.z_splits ? (int64_t)sp * p.z_slab + (int64_t)p.M * p.R : origin, 4);
+#pragma unroll
+          for (int i = 0; i < NP; ++i)
+            v[k][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(w.rsrc, (int)off[i], 0, 0));
+        }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+#pragma unroll
+          for (int k = 0; k < GROUP; ++k) {
+            if (g == 0 && k == 0) sum[i] = make_float4(v[0][i].x, v[0][i].y, v[0][i].z, v[0][i].w);
+            else { sum[i].x += v[k][i].x; sum[i].y += v[k][i].y; sum[i].z += v[k][i].z; sum[i].w += v[k][i].w; }
+          }
+        }
       }
-      float4 s = v[0];
+    }
 #pragma unroll
-      for (int k = 1; k < MAXS; ++k) { s.x += v[k].x; s.y += v[k].y; s.z += v[k].z; s.w += v[k].w; }
+    for (int i = 0; i < NP; ++i) {
+      const int piece = i * 256 + tid;
+      const int r = piece / PPR, c = (piece % PPR) * 4;
       uint2 w;
-      w.x = pack_bf16x2(s.x, s.y);
-      w.y = pack_bf16x2(s.z, s.w);
+      w.x = pack_bf16x2(sum[i].x, sum[i].y);
+      w.y = pack_bf16x2(sum[i].z, sum[i].w);
       *reinterpret_cast<uint2*>(Zs + r * L::Z_LD + c) = w;
     }
   }
