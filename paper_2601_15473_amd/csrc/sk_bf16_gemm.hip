@@ -121,6 +121,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
   constexpr int NMMA = TM * TN;
   constexpr int NVM = TA::PIECES + TB::PIECES;
 
+  // This lane's bias values (four columns per 8-column group of each 32-column block),
+  // fetched before the main loop so the epilogue does not wait for them; through a
+  // buffer window of N elements (none without a bias), so no lane needs a branch.
+  constexpr bool HAS_BIAS = sizeof(OutT) == 2;
+  uint2 bias_r[HAS_BIAS ? TN : 1][4];
+  if constexpr (HAS_BIAS) {
+    const GWindow bias_w = make_window(p.bias, 0, p.bias != nullptr ? p.N : 0, 2);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+        const int gn = n0 + wn * WN + j * 32 + q * 8 + (lane >> 5) * 4;
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(bias_w.rsrc, gn * 2, 0, 0);
+        bias_r[j][q] = make_uint2(v.x, v.y);
+      }
+  }
+
   // Iteration shape (PF == 1): the global loads of chunk kc + 1 are issued during k
   // steps 0 and 1 of chunk kc and stored to the other LDS buffer during k step 3.
   // Chunks past the end of the k range load as zeros: no branch around any load.
@@ -207,7 +225,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
   unsigned char* const stage = smem + wave * (32 * EP_LD);
   OutT* __restrict__ C = static_cast<OutT*>(p.C) +
                          (sizeof(OutT) == 4 ? (int64_t)split * p.M * p.ldc : (int64_t)0);
-  const bf16* __restrict__ bias = static_cast<const bf16*>(p.bias);
   const float scale = p.scale;
   const int wn0 = n0 + wn * WN;  // first global column of this wave
   const int n_store = p.n_store > 0 ? p.n_store : p.N;
@@ -224,8 +241,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e] * scale;
         if (sizeof(OutT) == 2) {
-          if (bias != nullptr && wn0 + c < p.N) {
-            const uint2 bb = *reinterpret_cast<const uint2*>(bias + wn0 + c);
+          if constexpr (HAS_BIAS) {
+            const uint2 bb = bias_r[j][q];
             v[0] += bf16_bits_to_float(bb.x & 0xffffu);
             v[1] += bf16_bits_to_float(bb.x >> 16);
             v[2] += bf16_bits_to_float(bb.y & 0xffffu);
@@ -317,15 +334,17 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
 
 template <bool A_KC, bool B_KC, typename OutT, bool COLSUM>
 static hipError_t launch_tiles(int tile, const GemmArgs& a, hipStream_t s) {
+  // the 256 x 256 tiles have no registers left for the column sums
+  if (COLSUM && (tile == TILE_256x256 || tile == TILE_256x256_W8)) return hipErrorInvalidValue;
   switch (tile) {
-    case TILE_256x256: return launch_cfg<256, 256, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_256x256: return launch_cfg<256, 256, 2, 2, A_KC, B_KC, OutT, false>(a, s);
     case TILE_128x128: return launch_cfg<128, 128, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
     case TILE_128x64: return launch_cfg<128, 64, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
     case TILE_64x128: return launch_cfg<64, 128, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
     case TILE_64x64: return launch_cfg<64, 64, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
     case TILE_256x128: return launch_cfg<256, 128, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
     case TILE_128x256: return launch_cfg<128, 256, 2, 2, A_KC, B_KC, OutT, COLSUM>(a, s);
-    case TILE_256x256_W8: return launch_cfg<256, 256, 2, 4, A_KC, B_KC, OutT, COLSUM>(a, s);
+    case TILE_256x256_W8: return launch_cfg<256, 256, 2, 4, A_KC, B_KC, OutT, false>(a, s);
     default: return hipErrorInvalidValue;
   }
 }

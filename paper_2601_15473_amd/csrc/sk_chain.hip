@@ -315,6 +315,24 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   load_b2(rb0, 0);
   load_b2(rb1, 1);
 
+  // bias through a buffer window of N elements (zero elements when there is no bias:
+  // every load then returns zero)
+  const GWindow bias_w = make_window(p.bias, 0, p.bias != nullptr ? p.N : 0, 2);
+  // this lane's 4 x 4 bias values of tile jt; always fetched one tile ahead of its use
+  // (a tile's MFMAs are shorter than a trip to L2)
+  auto load_bias = [&](uint2 (&bv)[4], int jt) {
+    const int n0 = (t_begin + jt) * CS_BN;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int cc = wave * 32 + q * 8 + (lane >> 5) * 4;
+      typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(bias_w.rsrc, (n0 + cc) * 2, 0, 0);
+      bv[q] = make_uint2(v.x, v.y);
+    }
+  };
+  uint2 bv0[4], bv1[4];
+  load_bias(bv0, 0);
+
   // ---------------- the intermediate tile Zt -> LDS ----------------
   if (FUSED) {
     typedef typename L::TA TA;
@@ -460,22 +478,6 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
 
   bf16* __restrict__ C = static_cast<bf16*>(p.C);
   const float scale = p.scale;
-  // bias through a buffer window of N elements (zero elements when there is no bias:
-  // every load then returns zero)
-  const GWindow bias_w = make_window(p.bias, 0, p.bias != nullptr ? p.N : 0, 2);
-
-  // this lane's 4 x 4 bias values of tile jt (issued before the prefetch of B2, so the
-  // epilogue does not have to wait for that prefetch to land)
-  auto load_bias = [&](uint2 (&bv)[4], int jt) {
-    const int n0 = (t_begin + jt) * CS_BN;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int cc = wave * 32 + q * 8 + (lane >> 5) * 4;
-      typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(bias_w.rsrc, (n0 + cc) * 2, 0, 0);
-      bv[q] = make_uint2(v.x, v.y);
-    }
-  };
 
   // one [64 x 128] output tile: wave w owns columns 32 w .. 32 w + 31 of it
   auto tile = [&](int jt, const bf16* Bs, const uint2 (&bv)[4]) {
@@ -520,18 +522,17 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
 
   for (int jt = 0; jt < my_tiles; jt += 2) {
     // tile jt sits in buffer 0; set 1 holds tile jt + 1
-    uint2 bv[4];
-    load_bias(bv, jt);
+    load_bias(bv1, jt + 1);
     load_b2(rb0, jt + 2);
     __builtin_amdgcn_sched_barrier(0);  // keep the new loads ahead of the wait for the old ones
-    tile(jt, Bbuf, bv);
+    tile(jt, Bbuf, bv0);
     __builtin_amdgcn_sched_barrier(0);
     TB2::store(Bbuf + TB2::ELEMS, rb1, tid);
     __syncthreads();
-    load_bias(bv, jt + 1);
+    load_bias(bv0, jt + 2);
     load_b2(rb1, jt + 3);
     __builtin_amdgcn_sched_barrier(0);
-    tile(jt + 1, Bbuf + TB2::ELEMS, bv);  // computes on zeros and stores nothing past the run
+    tile(jt + 1, Bbuf + TB2::ELEMS, bv1);  // computes on zeros and stores nothing past the run
     __builtin_amdgcn_sched_barrier(0);
     TB2::store(Bbuf, rb0, tid);
     __syncthreads();
