@@ -1,0 +1,92 @@
+"""The PyTorch surface (autograd Function + nn.Module) over libsk.
+
+GPU tests compare what autograd returns with the fp64 oracle on the module's own
+stored weights; the CPU tests check that nothing computes without a GPU."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sklinear as O
+
+
+def split(S_cat, U_cat, l, k):
+    """[in, l*k], [l*k, out] -> oracle form S [l, in, k], U [l, k, out] in fp64."""
+    S = np.stack([S_cat[:, i * k:(i + 1) * k] for i in range(l)])
+    U = np.stack([U_cat[i * k:(i + 1) * k, :] for i in range(l)])
+    return S.astype(np.float64), U.astype(np.float64)
+
+
+def test_no_cpu_path():
+    from paper_2601_15473_amd import nn as sknn
+    with pytest.raises(RuntimeError, match="GPU only"):
+        sknn.SKLinear(64, 64, 1, 16, device="cpu")
+    x = torch.zeros(4, 32)
+    S = torch.zeros(32, 16)
+    U = torch.zeros(16, 48)
+    with pytest.raises(RuntimeError, match="GPU only"):
+        sknn.sklinear(x, S, U, None, 1, 16)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,tol", [(torch.bfloat16, 2e-2), (torch.float32, 1e-4)], ids=["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(5, 40, 96), (333, 96)], ids=["batched", "flat"])
+def test_autograd_matches_oracle(dtype, tol, shape):
+    from paper_2601_15473_amd import nn as sknn
+    from skgpu import rel_err, to_f64
+    l, k, d_out = 3, 16, 80
+    print(f"case nn {dtype} x{shape} -> {d_out} l={l} k={k}", flush=True)
+    m = sknn.SKLinear(shape[-1], d_out, l, k, bias=True, dtype=dtype, seed=11)
+    g = torch.Generator().manual_seed(12)
+    x = torch.randn(*shape, generator=g).to(dtype).cuda().requires_grad_(True)
+    dY = torch.randn(*shape[:-1], d_out, generator=g).to(dtype).cuda()
+    y = m(x)
+    assert y.shape == dY.shape and y.dtype == dtype
+    y.backward(dY)
+    S, U = split(to_f64(m.S_cat), to_f64(m.U_cat), l, k)
+    x64 = to_f64(x).reshape(-1, shape[-1])
+    dY64 = to_f64(dY).reshape(-1, d_out)
+    want = dict(
+        y=O.forward(x64, S, U, to_f64(m.bias)),
+        dX=O.grad_input(dY64, S, U),
+        dU=O.grad_factors(x64, S, dY64).reshape(l * k, d_out),
+        db=O.grad_bias(dY64),
+    )
+    got = dict(y=to_f64(y).reshape(-1, d_out), dX=to_f64(x.grad).reshape(-1, shape[-1]),
+               dU=to_f64(m.U_cat.grad), db=to_f64(m.bias.grad))
+    assert m.S_cat.requires_grad is False
+    for n in want:
+        e = rel_err(got[n], want[n])
+        print(f"   {n}: {e:.2e}", flush=True)
+        assert e <= tol, (n, e)
+
+
+@pytest.mark.gpu
+def test_from_linear_keeps_the_dense_weights():
+    """U_i = S_i^T W^T: checked against the product formed in fp64 on the host, and the
+    sketched output approaches the dense one as l*k grows (E[S_i S_i^T] = I)."""
+    from paper_2601_15473_amd import nn as sknn
+    from skgpu import rel_err, to_f64
+    torch.manual_seed(3)
+    dense = torch.nn.Linear(64, 48).cuda()
+    x = torch.randn(200, 64, device="cuda")
+    errs = []
+    for l, k in ((1, 16), (8, 64)):
+        m = sknn.SKLinear.from_linear(dense, l, k, dtype=torch.float32, seed=5)
+        want_U = to_f64(m.S_cat).T @ to_f64(dense.weight).T
+        assert rel_err(to_f64(m.U_cat), want_U) <= 1e-5
+        assert torch.equal(m.bias, dense.bias)
+        with torch.no_grad():
+            y, ref = m(x), dense(x)
+        errs.append(float((y - ref).norm() / ref.norm()))
+    print("   relative distance to the dense layer:", errs, flush=True)
+    assert errs[1] < 0.5 * errs[0]
+
+
+@pytest.mark.gpu
+def test_no_grad_inputs_skip_their_kernels():
+    from paper_2601_15473_amd import nn as sknn
+    m = sknn.SKLinear(32, 48, 2, 16, bias=False, dtype=torch.bfloat16, seed=1)
+    x = torch.randn(10, 32).bfloat16().cuda()          # no grad wanted for x
+    m(x).sum().backward()
+    assert m.U_cat.grad is not None and m.U_cat.grad.dtype == torch.bfloat16
+    assert x.grad is None and m.bias is None
