@@ -52,7 +52,18 @@ LLM_MLP = Workload("c4_llm_mlp", 16384, 4096, 11008, 8, 256, "bf16", x_dist="stu
 
 ALL = (TINY, BERT_BASE_FFN_UP) + BERT_BASE_PROJ + (
     BERT_LARGE_FFN_UP, BERT_LARGE_FFN_DOWN, LLM_MLP)
-BY_NAME = {w.name: w for w in ALL}
+
+# The paper's own runtime grid for this layer (Sec. 4.1, Fig. 1): square layers of
+# 8192 features, l in {1, 2, 3}, k in {16 .. 512}; the text gives no batch size, so the
+# token count is this repository's choice.  l = 3 makes the 1/l scale inexact in binary.
+PAPER_GRID_FEATURES = 8192
+PAPER_GRID_TOKENS = 4096
+PAPER_GRID = tuple(
+    Workload(f"grid8192_l{l}_k{k}", PAPER_GRID_TOKENS, PAPER_GRID_FEATURES, PAPER_GRID_FEATURES,
+             l, k, "bf16")
+    for l in (1, 2, 3) for k in (16, 32, 64, 128, 256, 512))
+
+BY_NAME = {w.name: w for w in ALL + PAPER_GRID}
 
 
 def scaled(w: Workload, **changes) -> Workload:

@@ -61,7 +61,11 @@ SMALL = [
     W.scaled(W.BERT_LARGE_FFN_UP, tokens=600),
     W.scaled(W.BERT_LARGE_FFN_DOWN, tokens=600),
     W.scaled(W.LLM_MLP, tokens=300),
-] + [W.scaled(w, tokens=700) for w in W.BERT_BASE_PROJ]
+] + [W.scaled(w, tokens=700) for w in W.BERT_BASE_PROJ] + [
+    # the paper's own grid (square 8192 layers); l = 3 makes the 1/l scale inexact
+    W.scaled(W.BY_NAME["grid8192_l3_k16"], tokens=200),
+    W.scaled(W.BY_NAME["grid8192_l3_k512"], tokens=200),
+]
 
 
 @pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
