@@ -38,6 +38,8 @@ CALL_KERNELS = {
     "bwd_input": ["gemm_bf16_kernel (split-K, NT)", "chain_small_kernel (expand)"],
     "bwd_weight": ["gemm_bf16_kernel (Z^T)", "gemm_bf16_kernel (split-K, column sums)",
                    "reduce_splits_kernel"],
+    "bwd_weight_first": ["gemm_bf16_kernel (dY.U^T)", "gemm_bf16_kernel (split-K, x^T.G)",
+                         "reduce_splits_kernel"],
 }
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
@@ -57,8 +59,12 @@ def algorithmic(w, op):
         b = e * (T * (i + o) + R * (i + o) + o)
     elif op == "bwd_input":
         b = e * (T * (i + o) + R * (i + o))
-    else:
+    elif op == "bwd_weight":
         b = e * (T * (i + o) + i * R) + 4 * (R * o + o)
+    else:  # bwd_weight_first: x, dY and the fixed half of the second stage in, dA out
+        h = R // 2
+        flops = 2 * T * h * (i + o)
+        b = e * (T * (i + o) + h * o) + 4 * i * h
     return flops, b
 
 
@@ -73,6 +79,9 @@ def main():
     ap.add_argument("--no-dense-context", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count")
+    ap.add_argument("--two-sided", action="store_true",
+                    help="the two-sided reading of the layer: half of the workload's terms on each "
+                         "side (same stage-matrix shapes), four calls per step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device-to-device copy (for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -83,7 +92,7 @@ def main():
     import torch
     from paper_2601_15473_amd import libsk as sk
     from paper_2601_15473_amd import workloads as W
-    from paper_2601_15473_amd.device import DeviceLayer
+    from paper_2601_15473_amd.device import DeviceLayer, TwoSidedDeviceLayer
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -91,7 +100,13 @@ def main():
     if args.tokens:
         w = W.scaled(w, tokens=args.tokens)
     sk.sk_set_plan(args.plan)
-    tensors = W.generate(w)
+    if args.two_sided:
+        if w.l % 2:
+            sys.exit("bench.py: --two-sided needs an even number of terms to split over the two sides")
+        tensors = W.generate_two_sided(W.scaled(w, l=w.l // 2))
+        DeviceLayer = TwoSidedDeviceLayer
+    else:
+        tensors = W.generate(w)
 
     # Buffer sets: enough copies that a full rotation exceeds twice the Infinity Cache.
     one = DeviceLayer(tensors, sk, poison=False)
@@ -101,7 +116,7 @@ def main():
     sets = [one] + [DeviceLayer(tensors, sk, poison=False) for _ in range(n_sets - 1)]
 
     stream = torch.cuda.Stream()
-    ops = ("fwd", "bwd_input", "bwd_weight")
+    ops = ("fwd", "bwd_input", "bwd_weight") + (("bwd_weight_first",) if args.two_sided else ())
 
     def call(d, op):
         st = getattr(d, op)(stream)
@@ -161,7 +176,8 @@ def main():
         achieved, peak, unit = b_dom / per_op[dom]["ms"] / 1e6, HBM_PEAK_GBS, "GB/s"
     else:
         achieved, peak, unit = f_dom / per_op[dom]["ms"] / 1e9, peak_tf, "TFLOP/s"
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom)) if args.plan == 0 and not args.tokens else None
+    traffic = (MEASURED_TRAFFIC_BYTES.get((w.name, dom))
+               if args.plan == 0 and not args.tokens and not args.two_sided else None)
     roofline = {
         "bound": bound, "kernel": f"sk_linear_{dom}", "launch": "one call of the entry point",
         "kernels_in_call": CALL_KERNELS[dom] if w.R <= 128 and w.dtype == "bf16" else None,
@@ -179,7 +195,8 @@ def main():
         "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "tokens": w.tokens, "in": w.d_in, "out": w.d_out,
+        "config": {"workload": w.name + (" (two-sided: %d + %d terms)" % (w.l // 2, w.l // 2) if args.two_sided else ""),
+                   "tokens": w.tokens, "in": w.d_in, "out": w.d_out,
                    "l": w.l, "k": w.k, "plan": args.plan, "buffer_sets": n_sets,
                    "cache": "cold (buffer sets rotate, total > 2x Infinity Cache)"},
         "tflops": flops_step / (ms_step * 1e-3) / 1e12,
@@ -218,11 +235,22 @@ def main():
         from oracle import sklinear as O
         v = {n: a.astype(np.float64) for n, a in tensors.value.items()}
 
-        def oracle_step():
-            O.forward(v["x"], v["S"], v["U"], v.get("b"))
-            O.grad_input(v["dY"], v["S"], v["U"])
-            O.grad_factors(v["x"], v["S"], v["dY"])
-            O.grad_bias(v["dY"])
+        if args.two_sided:
+            from oracle import sklinear_two_sided as O2
+            terms = (v["S1"], v["U1"], v["U2"], v["S2"])
+
+            def oracle_step():
+                O2.forward(v["x"], *terms, v["b"])
+                O2.grad_input(v["dY"], *terms)
+                O2.grad_second_stage(v["x"], v["S1"], v["dY"])
+                O2.grad_first_stage(v["x"], v["S2"], v["dY"])
+                O2.grad_bias(v["dY"])
+        else:
+            def oracle_step():
+                O.forward(v["x"], v["S"], v["U"], v.get("b"))
+                O.grad_input(v["dY"], v["S"], v["U"])
+                O.grad_factors(v["x"], v["S"], v["dY"])
+                O.grad_bias(v["dY"])
         oracle_step()
         reps, t_begin = 0, time.perf_counter()
         while True:

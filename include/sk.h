@@ -58,7 +58,12 @@ typedef enum {
 
 typedef enum { SK_F32 = 0, SK_BF16 = 1 } sk_dtype;
 
-typedef enum { SK_OP_FWD = 0, SK_OP_BWD_INPUT = 1, SK_OP_BWD_WEIGHT = 2 } sk_op;
+typedef enum {
+  SK_OP_FWD = 0,
+  SK_OP_BWD_INPUT = 1,
+  SK_OP_BWD_WEIGHT = 2,
+  SK_OP_BWD_WEIGHT_FIRST = 3 /* sized so that it serves any column range */
+} sk_op;
 
 /*
  * Forward (Sec. 3.1):  y = (1/l) * (x . S_cat) . U_cat + bias.
@@ -97,6 +102,32 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
                                float* dbias, int64_t tokens, int64_t in, int64_t out, int32_t l,
                                int32_t k, sk_dtype dtype, void* workspace,
                                size_t workspace_bytes, void* stream);
+
+/*
+ * Gradient of learned columns of the FIRST stage matrix (two-sided layers).
+ *
+ * The paper's size rule (Sec. 4.1) counts a sketched layer as 2 l k (in + out)
+ * numbers, which fits a layer of 2 l terms: l that sketch the input side,
+ * (x . S1_i) . U1_i, and l that sketch the output side, (x . U2_i) . S2_i^T with
+ * U2_i (in x k) learned and S2_i (out x k) fixed, averaged over all 2 l.  That layer
+ * is the same two-stage chain with 2 l terms,
+ *     S_cat = [S1 | U2]  [in, 2lk],     U_cat = [U1 ; S2^T]  [2lk, out],
+ * so sk_linear_fwd, sk_linear_bwd_input and sk_linear_bwd_weight serve it unchanged
+ * with 2 l passed as `l` (the rows of dU_cat that belong to S2^T are gradients of
+ * fixed numbers and are simply not used).  What the chain lacks is the gradient of
+ * the learned first-stage columns, which this call computes for a column range:
+ *     dA = (1/l) * x^T . (dY . U_cat[col_begin .. col_begin+col_count, :]^T)
+ *   x [tokens, in], U_cat [R, out], dY [tokens, out],
+ *   dA [in, col_count] fp32, dense (output): column j is the gradient of column
+ *   col_begin + j of S_cat.  col_begin and col_count are multiples of 16,
+ *   col_count >= 16, col_begin + col_count <= R (else SK_ERR_INVALID_ARG).
+ * For the two-sided layer: l = 2 * (terms per side), col_begin = col_count = R / 2.
+ * Fixed-order reduction over tokens (bit-reproducible), as in sk_linear_bwd_weight.
+ */
+sk_status sk_linear_bwd_weight_first(const void* x, const void* U_cat, const void* dY, float* dA,
+                                     int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                                     int64_t col_begin, int64_t col_count, sk_dtype dtype,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Bytes of workspace that `op` needs for these sizes (0 when it needs none).

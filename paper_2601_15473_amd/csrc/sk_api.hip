@@ -83,57 +83,75 @@ struct WeightPlan {
   size_t total() const { return z_bytes + part_bytes + csum_bytes; }
 };
 
-// Split of the token contraction of dU = Z^T . dY.  The output (R x out, fp32) is
-// small, and every split writes and re-reads a slab of it, so: as few splits as fill
-// the chip, at least 256 tokens each, summed in a fixed order (deterministic).
-WeightPlan plan_weight(const Shape& s) {
-  WeightPlan w{};
+// A contraction over the token axis with a small fp32 output [M, N] (a weight gradient):
+// tile and split of the tokens.  Every split writes and re-reads a slab of the output,
+// so: as few splits as fill the chip, at least 256 tokens each, summed in a fixed
+// order (deterministic).
+struct TokenPlan {
+  int tile;            // bf16 tile configuration; -1 for fp32 (one tile shape)
+  bool big_tile;       // 256 x 256: no registers left for column sums in the kernel
+  int splits, k_per_split;
+};
+
+TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tunable) {
+  TokenPlan w{};
   int bm, bn;
-  if (s.dtype == SK_BF16) {
-    w.tile = s.R > 64 ? TILE_128x64 : TILE_64x64;
-    if (((s.R + 255) / 256) * ((s.out + 255) / 256) >= NUM_CUS) {
-      w.tile = TILE_256x256_W8;
-      w.own_colsum = true;
-    } else if (((s.R + 127) / 128) * ((s.out + 127) / 128) >= NUM_CUS) w.tile = TILE_128x128;
-    if (const char* e = getenv("SK_TUNE_WTILE")) {  // tuning experiments only
-      w.tile = atoi(e);
-      w.own_colsum = w.tile == TILE_256x256_W8 || w.tile == TILE_256x256;
-    }
+  if (dtype == SK_BF16) {
+    w.tile = M > 64 ? TILE_128x64 : TILE_64x64;
+    if (((M + 255) / 256) * ((N + 255) / 256) >= NUM_CUS) w.tile = TILE_256x256_W8;
+    else if (((M + 127) / 128) * ((N + 127) / 128) >= NUM_CUS) w.tile = TILE_128x128;
+    if (const char* e = tunable ? getenv("SK_TUNE_WTILE") : nullptr) w.tile = atoi(e);  // tuning experiments only
+    w.big_tile = w.tile == TILE_256x256_W8 || w.tile == TILE_256x256;
     tile_dims(w.tile, bm, bn);
-    w.ldz = (s.T + 63) / 64 * 64;
-    w.z_bytes = align_up((size_t)s.R * w.ldz * 2);
   } else {
     w.tile = -1;
     bm = F32_BM; bn = F32_BN;
-    w.ldz = s.R;
-    w.z_bytes = align_up((size_t)s.T * s.R * 4);
   }
-  const int64_t tiles = ((s.R + bm - 1) / bm) * ((s.out + bn - 1) / bn);
+  const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
   // Pick the split count with the least modelled time: rounds of work-groups over the
   // chip x tokens per split x the tile's time per token, plus writing and re-reading one
   // fp32 slab per split.  Rates are measured ones (flop/s one work-group sustains; HBM
   // bytes/s); the model only has to rank the candidates.
-  const double wg_rate = s.dtype != SK_BF16 ? 0.3e12 : bm * bn >= 256 * 256 ? 5.0e12 : bm * bn >= 128 * 128 ? 3.5e12
-                         : bm * bn >= 128 * 64 ? 2.2e12 : 1.5e12;
+  const double wg_rate = dtype != SK_BF16 ? 0.3e12 : bm * bn >= 256 * 256 ? 5.0e12
+                         : bm * bn >= 128 * 128 ? 3.5e12 : bm * bn >= 128 * 64 ? 2.2e12 : 1.5e12;
   const double t_token = 2.0 * bm * bn / wg_rate;
-  const double t_slab = (double)s.R * s.out * 8.0 / 4.0e12;
-  int64_t max_splits = (s.T + 255) / 256;   // at least 256 tokens each
+  const double t_slab = (double)M * N * 8.0 / 4.0e12;
+  int64_t max_splits = (T + 255) / 256;   // at least 256 tokens each
   if (max_splits > 32) max_splits = 32;
-  int64_t splits = 1, kps = (s.T + 63) / 64 * 64;
+  int64_t splits = 1, kps = (T + 63) / 64 * 64;
   double best = -1.0;
   for (int64_t sp = 1; sp <= max_splits; ++sp) {
-    int64_t k = (s.T + sp - 1) / sp;
+    int64_t k = (T + sp - 1) / sp;
     k = (k + 63) / 64 * 64;
-    const int64_t sp_eff = (s.T + k - 1) / k;
+    const int64_t sp_eff = (T + k - 1) / k;
     const int64_t rounds = (tiles * sp_eff + NUM_CUS - 1) / NUM_CUS;
     const double t = rounds * k * t_token + (sp_eff > 1 ? sp_eff * t_slab + 2.0e-6 : 0.0);
     if (best < 0.0 || t < best) { best = t; splits = sp_eff; kps = k; }
   }
-  if (const char* e = getenv("SK_TUNE_WSPLITS")) {  // tuning experiments only
+  if (const char* e = tunable ? getenv("SK_TUNE_WSPLITS") : nullptr) {  // tuning experiments only
     splits = atoi(e);
-    kps = ((s.T + splits - 1) / splits + 63) / 64 * 64;
-    splits = (s.T + kps - 1) / kps;
+    kps = ((T + splits - 1) / splits + 63) / 64 * 64;
+    splits = (T + kps - 1) / kps;
   }
+  w.splits = (int)splits;
+  w.k_per_split = (int)kps;
+  return w;
+}
+
+// dU = Z^T . dY with Z recomputed: where its pieces live in the workspace.
+WeightPlan plan_weight(const Shape& s) {
+  WeightPlan w{};
+  const TokenPlan t = plan_tokens(s.R, s.out, s.T, s.dtype, true);
+  w.tile = t.tile;
+  w.own_colsum = t.big_tile;
+  if (s.dtype == SK_BF16) {
+    w.ldz = (s.T + 63) / 64 * 64;
+    w.z_bytes = align_up((size_t)s.R * w.ldz * 2);
+  } else {
+    w.ldz = s.R;
+    w.z_bytes = align_up((size_t)s.T * s.R * 4);
+  }
+  const int64_t splits = t.splits, kps = t.k_per_split;
   w.splits = (int)splits;
   w.k_per_split = (int)kps;
   w.colsum_splits = w.splits;
@@ -227,6 +245,14 @@ int chain_slices(int64_t T, int64_t N, int R) {
   return (int)sl;
 }
 
+// Workspace of the first-stage gradient for nc columns: G = dY . U_sub^T [T, nc] in the
+// storage type, then the token-split slabs of dA [in, nc].
+size_t first_stage_bytes(const Shape& s, int64_t nc) {
+  const TokenPlan t = plan_tokens(s.in, nc, s.T, s.dtype, false);
+  return align_up((size_t)s.T * nc * s.esize) +
+         (t.splits > 1 ? align_up((size_t)t.splits * s.in * nc * 4) : 0);
+}
+
 size_t workspace_for(sk_op op, const Shape& s) {
   const size_t mid = align_up((size_t)s.T * s.R * s.esize);  // Z or G
   switch (op) {
@@ -242,6 +268,16 @@ size_t workspace_for(sk_op op, const Shape& s) {
     }
     case SK_OP_BWD_WEIGHT:
       return plan_weight(s).total();
+    case SK_OP_BWD_WEIGHT_FIRST: {
+      // the maximum over every admissible column count (narrow ranges split the tokens
+      // further), so one buffer serves any range
+      size_t need = 0;
+      for (int64_t nc = 16; nc <= s.R; nc += 16) {
+        const size_t b = first_stage_bytes(s, nc);
+        if (b > need) need = b;
+      }
+      return need;
+    }
   }
   return 0;
 }
@@ -289,7 +325,9 @@ int sk_set_plan(int plan) {
 size_t sk_linear_workspace_bytes(sk_op op, int64_t tokens, int64_t in, int64_t out, int32_t l,
                                  int32_t k, sk_dtype dtype) {
   Shape s;
-  if (op != SK_OP_FWD && op != SK_OP_BWD_INPUT && op != SK_OP_BWD_WEIGHT) return (size_t)-1;
+  if (op != SK_OP_FWD && op != SK_OP_BWD_INPUT && op != SK_OP_BWD_WEIGHT &&
+      op != SK_OP_BWD_WEIGHT_FIRST)
+    return (size_t)-1;
   if (check_shape(tokens, in, out, l, k, dtype, s) != SK_OK) return (size_t)-1;
   return workspace_for(op, s);
 }
@@ -449,6 +487,58 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
     r.splits = w.splits; r.splits2 = w.colsum_splits;
     e = launch_reduce_splits(r, hs);
     if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (sum of splits)");
+  }
+  return SK_OK;
+}
+
+sk_status sk_linear_bwd_weight_first(const void* x, const void* U_cat, const void* dY, float* dA,
+                                     int64_t tokens, int64_t in, int64_t out, int32_t l, int32_t k,
+                                     int64_t col_begin, int64_t col_count, sk_dtype dtype,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !U_cat || !dY || !dA) return SK_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(U_cat) || !aligned16(dY) || !aligned16(dA) || !aligned16(workspace))
+    return SK_ERR_INVALID_ARG;
+  Shape s;
+  const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
+  if (st != SK_OK) return st;
+  if (col_begin < 0 || col_count < 16 || col_begin % 16 != 0 || col_count % 16 != 0 ||
+      col_begin + col_count > s.R)
+    return SK_ERR_INVALID_ARG;
+  const int64_t nc = col_count;
+  if (!workspace || workspace_bytes < first_stage_bytes(s, nc)) return SK_ERR_WORKSPACE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const float scale = 1.0f / (float)l;
+  g_hip_error.clear();
+
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  void* G = ws;
+  float* part = reinterpret_cast<float*>(ws + align_up((size_t)s.T * nc * s.esize));
+  const unsigned char* U_sub = static_cast<const unsigned char*>(U_cat) + (size_t)col_begin * out * s.esize;
+
+  // G = dY . U_sub^T, rounded to the storage type like the input gradient's intermediate
+  hipError_t e = gemm(s, GEMM_NT, dense_args(dY, out, U_sub, out, G, nc, tokens, nc, out, 1.0f, nullptr), hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight_first (dY.U^T)");
+
+  // dA = scale * x^T . G, the token axis split in order
+  const TokenPlan t = plan_tokens(in, nc, tokens, dtype, false);
+  GemmArgs a{};
+  a.A = x; a.lda = in;
+  a.B = G; a.ldb = nc;
+  a.ldc = nc;
+  a.M = (int)in; a.N = (int)nc; a.K = (int)tokens;
+  a.splits = t.splits; a.k_per_split = t.k_per_split;
+  a.bias = nullptr; a.colsum = nullptr;
+  if (t.splits == 1) { a.C = dA; a.scale = scale; }
+  else { a.C = part; a.scale = 1.0f; }
+  e = dtype == SK_BF16 ? launch_gemm_bf16(GEMM_TN_F32_PLAIN, t.tile, a, hs)
+                       : launch_gemm_f32(GEMM_TN_F32, a, hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight_first (x^T.G)");
+  if (t.splits > 1) {
+    ReduceArgs r{};
+    r.part = part; r.out = dA; r.n = (int64_t)in * nc; r.scale = scale;
+    r.n2 = 0; r.splits = t.splits; r.splits2 = 1;
+    e = launch_reduce_splits(r, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight_first (sum of splits)");
   }
   return SK_OK;
 }

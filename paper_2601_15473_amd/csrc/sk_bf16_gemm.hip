@@ -354,6 +354,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStrea
     case GEMM_NN: return launch_tiles<true, false, bf16, false>(tile, a, s);
     case GEMM_NT: return launch_tiles<true, true, bf16, false>(tile, a, s);
     case GEMM_TN_F32: return launch_tiles<false, false, float, true>(tile, a, s);
+    case GEMM_TN_F32_PLAIN: return launch_tiles<false, false, float, false>(tile, a, s);
     case GEMM_NN_F32: return launch_tiles<true, false, float, false>(tile, a, s);
     case GEMM_TT: return launch_tiles<false, true, bf16, false>(tile, a, s);
     case GEMM_NN_F32_COLSUM: return launch_tiles<true, false, float, true>(tile, a, s);

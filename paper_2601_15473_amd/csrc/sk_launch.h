@@ -12,6 +12,7 @@ enum GemmKind : int {
   GEMM_NT_F32 = 4,  // as GEMM_NT, split-K          -> fp32 slabs
   GEMM_TT = 5,      // A [K,M], B [N,K]            -> storage type
   GEMM_NN_F32_COLSUM = 6,  // as GEMM_NN_F32, plus the column sums of B
+  GEMM_TN_F32_PLAIN = 7,   // as GEMM_TN_F32 without the column sums (any tile)
 };
 
 enum TileCfg : int {

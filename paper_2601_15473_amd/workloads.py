@@ -123,6 +123,47 @@ def _normal(rng, shape, var):
     return a
 
 
+def _store(w: Workload, raw: dict):
+    stored, value = {}, {}
+    for name, a in raw.items():
+        if w.dtype == "bf16":
+            bits = f32_to_bf16_bits(a)
+            stored[name] = bits
+            value[name] = bf16_bits_to_f32(bits)
+        elif w.dtype == "f32":
+            stored[name] = a
+            value[name] = a
+        else:
+            raise ValueError(w.dtype)
+    return stored, value
+
+
+def generate_two_sided(w: Workload) -> Tensors:
+    """Inputs of the two-sided reading of the layer: ``w.l`` terms per side.  Draw order:
+    x, S1 terms, U1 terms, U2 terms, S2 terms, b, dY.  Fixed sketches have variance 1/k,
+    learned factors 1/(2 l k).  Shapes: S1 [l,in,k], U1 [l,k,out], U2 [l,in,k], S2 [l,out,k].
+    ``A_cat``/``B_cat`` are the stage matrices of the equivalent chain of 2 l terms
+    ([S1 | U2] and [U1 ; S2^T]) in storage form -- a re-layout, no arithmetic."""
+    rng = np.random.default_rng(w.seed)
+    T, d_in, d_out, l, k = w.tokens, w.d_in, w.d_out, w.l, w.k
+    raw = {
+        "x": _normal(rng, (T, d_in), 1.0),
+        "S1": np.stack([_normal(rng, (d_in, k), 1.0 / k) for _ in range(l)]),
+        "U1": np.stack([_normal(rng, (k, d_out), 1.0 / (2 * l * k)) for _ in range(l)]),
+        "U2": np.stack([_normal(rng, (d_in, k), 1.0 / (2 * l * k)) for _ in range(l)]),
+        "S2": np.stack([_normal(rng, (d_out, k), 1.0 / k) for _ in range(l)]),
+        "b": _normal(rng, (d_out,), 0.01),
+        "dY": _normal(rng, (T, d_out), 1.0),
+    }
+    stored, value = _store(w, raw)
+    for d in (stored, value):
+        first = np.concatenate([d["S1"], d["U2"]], axis=0)                            # [2l, in, k]
+        second = np.concatenate([d["U1"], np.transpose(d["S2"], (0, 2, 1))], axis=0)  # [2l, k, out]
+        d["A_cat"] = np.ascontiguousarray(np.transpose(first, (1, 0, 2)).reshape(d_in, 2 * l * k))
+        d["B_cat"] = np.ascontiguousarray(second.reshape(2 * l * k, d_out))
+    return Tensors(w, stored, value)
+
+
 def generate(w: Workload, with_bias: bool = True) -> Tensors:
     rng = np.random.default_rng(w.seed)
     T, d_in, d_out, l, k = w.tokens, w.d_in, w.d_out, w.l, w.k
@@ -140,15 +181,5 @@ def generate(w: Workload, with_bias: bool = True) -> Tensors:
     raw = {"x": x, "S": S, "U": U, "dY": dY}
     if with_bias:
         raw["b"] = b
-    stored, value = {}, {}
-    for name, a in raw.items():
-        if w.dtype == "bf16":
-            bits = f32_to_bf16_bits(a)
-            stored[name] = bits
-            value[name] = bf16_bits_to_f32(bits)
-        elif w.dtype == "f32":
-            stored[name] = a
-            value[name] = a
-        else:
-            raise ValueError(w.dtype)
+    stored, value = _store(w, raw)
     return Tensors(w, stored, value)

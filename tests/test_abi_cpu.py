@@ -89,3 +89,19 @@ def test_check_raises():
         sk.check(sk.SK_ERR_UNSUPPORTED)
     assert e.value.status == sk.SK_ERR_UNSUPPORTED
     sk.check(sk.SK_OK)
+
+
+def test_first_stage_gradient_argument_checks():
+    T, i, o, l, k, dt = ARGS
+    R = l * k
+    f = sk.sk_linear_bwd_weight_first
+    big = 1 << 30
+    assert f(None, P, P, P, T, i, o, l, k, 0, R, dt, P, big) == sk.SK_ERR_INVALID_ARG
+    assert f(P, P, P, P + 4, T, i, o, l, k, 0, R, dt, P, big) == sk.SK_ERR_INVALID_ARG
+    for c0, nc in ((0, 0), (8, 16), (0, 24), (16, R), (-16, 16)):       # empty, misaligned, past the end
+        assert f(P, P, P, P, T, i, o, l, k, c0, nc, dt, P, big) == sk.SK_ERR_INVALID_ARG, (c0, nc)
+    assert f(P, P, P, P, T, i, o, l, k, 0, R, 7, P, big) == sk.SK_ERR_UNSUPPORTED
+    need = sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT_FIRST, *ARGS)
+    assert 0 < need < 2 ** 63
+    assert f(P, P, P, P, T, i, o, l, k, 0, R, dt, P, need - 1) == sk.SK_ERR_WORKSPACE
+    assert f(P, P, P, P, T, i, o, l, k, 0, R, dt, None, 0) == sk.SK_ERR_WORKSPACE
