@@ -131,6 +131,47 @@ def test_parity_llm_mlp_full_size_sampled(sk):
     assert torch.isfinite(dev.dU).all() and torch.isfinite(dev.db).all()
 
 
+def test_outputs_past_two_gib_sampled(sk):
+    """A token count that puts y and dY past 2^31 bytes (byte offsets no longer fit 32 bits
+    anywhere but inside one tile): c1's layer at 360 000 tokens, checked on sampled token
+    rows of y and dX (first, last and random ones) and sampled columns of dU and db."""
+    # (a seeded block of 36 000 tokens repeated ten times: drawing 1.4e9 fresh normals on
+    # the host would take minutes and add nothing to the check)
+    block = W.generate(W.scaled(W.BERT_BASE_FFN_UP, tokens=36_000, seed=31))
+    w = W.scaled(block.workload, tokens=360_000)
+    assert w.tokens * w.d_out * 2 > 2 ** 31
+    print(f"case {w.name} T={w.tokens} (outputs past 2 GiB, sampled)", flush=True)
+    sk.sk_set_plan(0)
+    rep = lambda d: {n: (np.tile(a, (10, 1)) if n in ("x", "dY") else a) for n, a in d.items()}  # noqa: E731
+    t = W.Tensors(w, rep(block.stored), rep(block.value))
+    dev = DeviceLayer(t, sk)
+    dev.run_all()
+    r = np.random.default_rng(7)
+    rows = np.sort(r.choice(w.tokens, 64, replace=False))
+    rows[0], rows[-1] = 0, w.tokens - 1
+    rows[1], rows[-2] = 2 ** 31 // (w.d_out * 2) - 1, 2 ** 31 // (w.d_out * 2) + 1   # either side of 2 GiB in y
+    rows = np.unique(rows)
+    cols = np.sort(r.choice(w.d_out, 24, replace=False))
+    cols[0], cols[-1] = 0, w.d_out - 1
+    v = t.value
+    S, U = v["S"].astype(np.float64), v["U"].astype(np.float64)
+    y = O.forward(v["x"][rows].astype(np.float64), S, U, v["b"].astype(np.float64))
+    dX = O.grad_input(v["dY"][rows].astype(np.float64), S, U)
+    dYc = v["dY"][:, cols].astype(np.float64)
+    dU = O.grad_factors(v["x"].astype(np.float64), S, dYc).reshape(w.R, len(cols))
+    db = O.grad_bias(dYc)
+    rows_t, cols_t = torch.from_numpy(rows).cuda(), torch.from_numpy(cols).cuda()
+    errs = dict(y=rel_err(to_f64(dev.y[rows_t]), y), dX=rel_err(to_f64(dev.dX[rows_t]), dX),
+                dU=rel_err(to_f64(dev.dU[:, cols_t]), dU), db=rel_err(to_f64(dev.db[cols_t]), db))
+    print("   errors:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= TOL["bf16"], (n, e)
+    # nothing left unwritten anywhere (the buffers start as NaN)
+    assert torch.isfinite(dev.y.view(torch.int16).view(torch.bfloat16)[-4096:].float()).all()
+    assert not torch.isnan(dev.dX.float().sum()) and not torch.isnan(dev.y[:100000].float().sum())
+    assert not torch.isnan(dev.y[100000:].float().sum())
+
+
 def test_forced_big_tiles(sk, monkeypatch):
     """The large-shape code paths (big tiles, the bias gradient from its own kernel)
     on a shape small enough for a full oracle pass."""
