@@ -38,6 +38,8 @@ CALL_KERNELS = {
     "bwd_input": ["gemm_bf16_kernel (split-K, NT)", "chain_small_kernel (expand)"],
     "bwd_weight": ["gemm_bf16_kernel (Z^T)", "gemm_bf16_kernel (split-K, column sums)",
                    "reduce_splits_kernel"],
+    "bwd": ["dual_gemm_kernel (dY.U^T split-K beside Z^T)", "gemm_bf16_kernel (split-K, column sums)",
+            "chain_small_kernel (expand, carrying the sum of the splits)"],
     "bwd_weight_first": ["gemm_bf16_kernel (dY.U^T)", "gemm_bf16_kernel (split-K, x^T.G)",
                          "reduce_splits_kernel"],
 }
@@ -61,6 +63,9 @@ def algorithmic(w, op):
         b = e * (T * (i + o) + R * (i + o))
     elif op == "bwd_weight":
         b = e * (T * (i + o) + i * R) + 4 * (R * o + o)
+    elif op == "bwd":  # both gradients: x and dY in once, dX, dU, db out
+        flops = 4 * T * R * (i + o)
+        b = e * (T * (2 * i + o) + R * (i + o)) + 4 * (R * o + o)
     else:  # bwd_weight_first: x, dY and the fixed half of the second stage in, dA out
         h = R // 2
         flops = 2 * T * h * (i + o)
@@ -79,6 +84,8 @@ def main():
     ap.add_argument("--no-dense-context", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count")
+    ap.add_argument("--single-call-backward", action="store_true",
+                    help="one step = sk_linear_fwd + sk_linear_bwd (both gradients in one call)")
     ap.add_argument("--two-sided", action="store_true",
                     help="the two-sided reading of the layer: half of the workload's terms on each "
                          "side (same stage-matrix shapes), four calls per step")
@@ -117,6 +124,10 @@ def main():
 
     stream = torch.cuda.Stream()
     ops = ("fwd", "bwd_input", "bwd_weight") + (("bwd_weight_first",) if args.two_sided else ())
+    if args.single_call_backward:
+        if args.two_sided:
+            sys.exit("bench.py: --single-call-backward and --two-sided do not combine")
+        ops = ("fwd", "bwd")
 
     def call(d, op):
         st = getattr(d, op)(stream)
@@ -151,6 +162,17 @@ def main():
     wall = time.perf_counter() - t0
     ms_step_warm = timed(lambda i: step(one), args.steps)
 
+    # ---- the same step with both gradients from one call (sk_linear_bwd), same protocol ----
+    ms_step_single = None
+    if not args.two_sided and not args.single_call_backward:
+        def step_single(d):
+            call(d, "fwd")
+            call(d, "bwd")
+        with torch.cuda.stream(stream):
+            for i in range(args.warmup):
+                step_single(sets[i % n_sets])
+        ms_step_single = timed(lambda i: step_single(sets[i % n_sets]), args.steps)
+
     # ---- per-call times, same protocol ----
     per_op = {}
     for op in ops:
@@ -177,7 +199,7 @@ def main():
     else:
         achieved, peak, unit = f_dom / per_op[dom]["ms"] / 1e9, peak_tf, "TFLOP/s"
     traffic = (MEASURED_TRAFFIC_BYTES.get((w.name, dom))
-               if args.plan == 0 and not args.tokens and not args.two_sided else None)
+               if args.plan == 0 and not args.tokens and not args.two_sided else None)  # none measured for 'bwd'
     roofline = {
         "bound": bound, "kernel": f"sk_linear_{dom}", "launch": "one call of the entry point",
         "kernels_in_call": CALL_KERNELS[dom] if w.R <= 128 and w.dtype == "bf16" else None,
@@ -198,6 +220,7 @@ def main():
         "config": {"workload": w.name + (" (two-sided: %d + %d terms)" % (w.l // 2, w.l // 2) if args.two_sided else ""),
                    "tokens": w.tokens, "in": w.d_in, "out": w.d_out,
                    "l": w.l, "k": w.k, "plan": args.plan, "buffer_sets": n_sets,
+                   "calls_per_step": list(ops),
                    "cache": "cold (buffer sets rotate, total > 2x Infinity Cache)"},
         "tflops": flops_step / (ms_step * 1e-3) / 1e12,
         "ms_per_step_warm": ms_step_warm,
@@ -205,6 +228,11 @@ def main():
         "per_call": per_op,
         "roofline": roofline,
     }
+    if ms_step_single is not None:
+        out["single_call_backward"] = {
+            "what": "the same step as sk_linear_fwd + sk_linear_bwd (both gradients in one call, "
+                    "kernels of the two gradients sharing launches); not used for `value`",
+            "ms_per_step": ms_step_single, "tokens_per_s": w.tokens / (ms_step_single * 1e-3)}
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")

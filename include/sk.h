@@ -62,7 +62,8 @@ typedef enum {
   SK_OP_FWD = 0,
   SK_OP_BWD_INPUT = 1,
   SK_OP_BWD_WEIGHT = 2,
-  SK_OP_BWD_WEIGHT_FIRST = 3 /* sized so that it serves any column range */
+  SK_OP_BWD_WEIGHT_FIRST = 3, /* sized so that it serves any column range */
+  SK_OP_BWD = 4               /* sk_linear_bwd: both gradients in one call */
 } sk_op;
 
 /*
@@ -102,6 +103,26 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
                                float* dbias, int64_t tokens, int64_t in, int64_t out, int32_t l,
                                int32_t k, sk_dtype dtype, void* workspace,
                                size_t workspace_bytes, void* stream);
+
+/*
+ * Both gradients in one call: what sk_linear_bwd_input followed by sk_linear_bwd_weight
+ * compute (same formulas, same outputs, same rounding points; the order of the fp32
+ * partial sums inside dX may differ from the separate call's, dU_cat and dbias are
+ * bit-identical to it), scheduled together.  For narrow sketches (bf16, R <= 128)
+ * kernels of the two gradients that do not depend on each other share launches --
+ * dY . U_cat^T runs beside the recomputation of x . S_cat, and the sum of the factor
+ * gradient's token splits rides on the kernel that expands dX -- three launches instead
+ * of five, which is most of the cost at BERT-base sizes.  Other shapes run the two
+ * gradients one after the other.
+ *   x [tokens, in], dY [tokens, out], S_cat [in, R], U_cat [R, out],
+ *   dX [tokens, in] (output), dU_cat [R, out] fp32 (output), dbias [out] fp32 (output) or NULL.
+ * Workspace: sk_linear_workspace_bytes(SK_OP_BWD, ...) (the two gradients' workspaces side
+ * by side, since they are in use at the same time).
+ */
+sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const void* U_cat,
+                        void* dX, float* dU_cat, float* dbias, int64_t tokens, int64_t in,
+                        int64_t out, int32_t l, int32_t k, sk_dtype dtype, void* workspace,
+                        size_t workspace_bytes, void* stream);
 
 /*
  * Gradient of learned columns of the FIRST stage matrix (two-sided layers).

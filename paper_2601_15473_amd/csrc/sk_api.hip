@@ -268,6 +268,8 @@ size_t workspace_for(sk_op op, const Shape& s) {
     }
     case SK_OP_BWD_WEIGHT:
       return plan_weight(s).total();
+    case SK_OP_BWD:
+      return workspace_for(SK_OP_BWD_INPUT, s) + workspace_for(SK_OP_BWD_WEIGHT, s);
     case SK_OP_BWD_WEIGHT_FIRST: {
       // the maximum over every admissible column count (narrow ranges split the tokens
       // further), so one buffer serves any range
@@ -326,7 +328,7 @@ size_t sk_linear_workspace_bytes(sk_op op, int64_t tokens, int64_t in, int64_t o
                                  int32_t k, sk_dtype dtype) {
   Shape s;
   if (op != SK_OP_FWD && op != SK_OP_BWD_INPUT && op != SK_OP_BWD_WEIGHT &&
-      op != SK_OP_BWD_WEIGHT_FIRST)
+      op != SK_OP_BWD_WEIGHT_FIRST && op != SK_OP_BWD)
     return (size_t)-1;
   if (check_shape(tokens, in, out, l, k, dtype, s) != SK_OK) return (size_t)-1;
   return workspace_for(op, s);
@@ -489,6 +491,79 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
     if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (sum of splits)");
   }
   return SK_OK;
+}
+
+sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const void* U_cat,
+                        void* dX, float* dU_cat, float* dbias, int64_t tokens, int64_t in,
+                        int64_t out, int32_t l, int32_t k, sk_dtype dtype, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  if (!x || !dY || !S_cat || !U_cat || !dX || !dU_cat) return SK_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(dY) || !aligned16(S_cat) || !aligned16(U_cat) || !aligned16(dX) ||
+      !aligned16(dU_cat) || !aligned16(dbias) || !aligned16(workspace))
+    return SK_ERR_INVALID_ARG;
+  Shape s;
+  const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
+  if (st != SK_OK) return st;
+  const size_t in_bytes = workspace_for(SK_OP_BWD_INPUT, s);
+  const size_t w_bytes = workspace_for(SK_OP_BWD_WEIGHT, s);
+  if (!workspace || workspace_bytes < in_bytes + w_bytes) return SK_ERR_WORKSPACE;
+  unsigned char* ws_in = static_cast<unsigned char*>(workspace);
+  unsigned char* ws_w = ws_in + in_bytes;
+
+  // The shared-launch schedule needs the shapes the narrow-sketch plans produce: the input
+  // gradient as split-K slabs + expand, Z^T on the 64 x 64 tile, split token contraction
+  // with the column sums riding on it.
+  const SketchPlan q = plan_sketch(s, out);
+  const WeightPlan w = plan_weight(s);
+  const int z_tile = s.dtype == SK_BF16 ? choose_tile(s.R, tokens, in, 1) : -1;
+  const bool shared = s.dtype == SK_BF16 && chain_supported(s.R) && s.R <= 128 &&
+                      g_plan.load(std::memory_order_relaxed) == PLAN_AUTO && q.splits > 1 &&
+                      (q.tile == TILE_64x128 || q.tile == TILE_64x64) && z_tile == TILE_64x64 &&
+                      !w.own_colsum && w.splits > 1;
+  if (!shared) {
+    const sk_status a = sk_linear_bwd_input(dY, S_cat, U_cat, dX, tokens, in, out, l, k, dtype, ws_in,
+                                            in_bytes, stream);
+    if (a != SK_OK) return a;
+    return sk_linear_bwd_weight(x, S_cat, dY, dU_cat, dbias, tokens, in, out, l, k, dtype, ws_w, w_bytes,
+                                stream);
+  }
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const float scale = 1.0f / (float)l;
+  g_hip_error.clear();
+
+  // launch 1: G slabs = dY . U_cat^T (split over `out`)  beside  Z^T = S_cat^T . x^T
+  GemmArgs g = dense_args(dY, out, U_cat, out, ws_in, s.R, tokens, s.R, out, 1.0f, nullptr);
+  g.splits = q.splits; g.k_per_split = q.k_per_split;
+  void* Z = ws_w;
+  float* part = reinterpret_cast<float*>(ws_w + w.z_bytes);
+  float* cpart = reinterpret_cast<float*>(ws_w + w.z_bytes + w.part_bytes);
+  GemmArgs z = dense_args(S_cat, s.R, x, in, Z, w.ldz, s.R, tokens, in, 1.0f, nullptr);
+  z.n_store = (int)w.ldz;
+  hipError_t e = launch_dual_gemm_bf16(q.tile, g, z_tile, z, hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (dY.U^T beside x.S)");
+
+  // launch 2: dU slabs = Z^T . dY with the column sums of dY, the token axis split in order
+  GemmArgs a{};
+  a.A = Z; a.lda = w.ldz;
+  a.B = dY; a.ldb = out; a.ldc = out;
+  a.M = s.R; a.N = (int)out; a.K = (int)tokens;
+  a.splits = w.splits; a.k_per_split = w.k_per_split;
+  a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
+  e = launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (Z^T.dY)");
+
+  // launch 3: dX = scale * (sum of G slabs) . S_cat^T, carrying the sum of the dU and db slabs
+  ChainArgs c{};
+  c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
+  c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
+  c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
+  c.n_slices = chain_slices(tokens, in, s.R);
+  c.Z = ws_in; c.z_splits = q.splits; c.z_slab = (int64_t)tokens * s.R;
+  c.tail.part = part; c.tail.out = dU_cat; c.tail.n = (int64_t)s.R * out; c.tail.scale = scale;
+  c.tail.part2 = cpart; c.tail.out2 = dbias; c.tail.n2 = dbias ? out : 0; c.tail.scale2 = 1.0f;
+  c.tail.splits = w.splits; c.tail.splits2 = w.colsum_splits;
+  e = launch_chain_bf16(true, false, c, hs);
+  return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd (expand + sum of splits)");
 }
 
 sk_status sk_linear_bwd_weight_first(const void* x, const void* U_cat, const void* dY, float* dA,

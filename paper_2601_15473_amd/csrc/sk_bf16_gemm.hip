@@ -36,26 +36,37 @@ template <typename OutT> struct OutTraits;
 template <> struct OutTraits<bf16> { static constexpr int PIECE = 8; };    // 4 bf16
 template <> struct OutTraits<float> { static constexpr int PIECE = 16; };  // 4 fp32
 
+// One tile configuration of the GEMM: its work-group size, its LDS footprint and its body
+// (the work of one work-group, given the group's index in the launch and LDS of at
+// least LDS_BYTES).  The body is a device function so that one launch can carry the
+// work-groups of two independent GEMMs (dual_gemm_kernel below).
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
           bool COLSUM, int PF>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const GemmArgs p) {
-  constexpr int NTH = 64 * WAVES_M * WAVES_N;
+struct GemmTile {
+  static constexpr int NTH = 64 * WAVES_M * WAVES_N;
   typedef OpTile<BM, A_KC, BK, NTH> TA;
   typedef OpTile<BN, B_KC, BK, NTH> TB;
-  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
-  constexpr int STAGE = TA::ELEMS + TB::ELEMS;
-  constexpr int PIECE = OutTraits<OutT>::PIECE;
-  constexpr int EP_LD = WN * (int)sizeof(OutT) + PIECE;  // bytes per staged output row
-  constexpr int EP_BYTES = WAVES_M * WAVES_N * 32 * EP_LD;
-  constexpr int LDS_BYTES = (2 * STAGE * 2 > EP_BYTES) ? 2 * STAGE * 2 : EP_BYTES;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  static constexpr int STAGE = TA::ELEMS + TB::ELEMS;
+  static constexpr int PIECE = OutTraits<OutT>::PIECE;
+  static constexpr int EP_LD = WN * (int)sizeof(OutT) + PIECE;  // bytes per staged output row
+  static constexpr int EP_BYTES = WAVES_M * WAVES_N * 32 * EP_LD;
+  static constexpr int LDS_BYTES = (2 * STAGE * 2 > EP_BYTES) ? 2 * STAGE * 2 : EP_BYTES;
+  static __device__ __forceinline__ void run(const GemmArgs& p, int block, unsigned char* smem);
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
+          bool COLSUM, int PF>
+__device__ __forceinline__ void
+GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const GemmArgs& p, const int block,
+                                                                      unsigned char* const smem) {
   bf16* const lds = reinterpret_cast<bf16*>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   const int tiles = p.tiles_m * p.tiles_n;
-  const int id = xcd_remap(blockIdx.x, tiles * p.splits);
+  const int id = xcd_remap(block, tiles * p.splits);
   const int split = id / tiles;
   int tile_m, tile_n;
   tile_coords(id - split * tiles, p.tiles_m, p.tiles_n, tile_m, tile_n);
@@ -296,11 +307,35 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const
 
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
+          bool COLSUM, int PF>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(const GemmArgs p) {
+  typedef GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF> G;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[G::LDS_BYTES];
+  G::run(p, blockIdx.x, smem);
+}
+
+// Two independent GEMMs in one launch: the first `groups_a` work-groups run GA on `a`, the
+// rest run GB on `b`.  For small problems a kernel's fixed cost (launch, first trip to
+// memory, drain) is as large as its work, and two kernels that do not depend on each
+// other can share it; the chip co-schedules both kinds of work-group on every CU.
+template <class GA, class GB>
+__global__ __launch_bounds__(256) void dual_gemm_kernel(const GemmArgs a, const GemmArgs b,
+                                                        const int groups_a) {
+  static_assert(GA::NTH == 256 && GB::NTH == 256, "both halves run 256 threads per work-group");
+  constexpr int BYTES = GA::LDS_BYTES > GB::LDS_BYTES ? GA::LDS_BYTES : GB::LDS_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[BYTES];
+  if ((int)blockIdx.x < groups_a) GA::run(a, blockIdx.x, smem);
+  else GB::run(b, (int)blockIdx.x - groups_a, smem);
+}
+
 // Sums the split-K slabs in index order; see ReduceArgs.
+// (One piece per thread and no bounds test inside the slab loop: as many work-groups as
+// pieces allow matters more here than loads per thread.)
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const ReduceArgs p) {
   int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-  const float* part = p.part;
-  float* out = p.out;
+  const float* __restrict__ part = p.part;
+  float* __restrict__ out = p.out;
   int64_t n = p.n;
   float scale = p.scale;
   int splits = p.splits;
@@ -398,6 +433,28 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* 
     if (gc < cols)
       out[(int64_t)blockIdx.y * cols + gc] = ((part[0][i] + part[1][i]) + part[2][i]) + part[3][i];
   }
+}
+
+hipError_t launch_dual_gemm_bf16(int tile_a, GemmArgs a, int tile_b, GemmArgs b, hipStream_t s) {
+  typedef GemmTile<64, 128, 2, 2, true, true, float, false, 2> A128;   // GEMM_NT_F32, 64 x 128
+  typedef GemmTile<64, 64, 2, 2, true, true, float, false, 2> A64;     // GEMM_NT_F32, 64 x 64
+  typedef GemmTile<64, 64, 2, 2, false, true, bf16, false, 2> B64;     // GEMM_TT, 64 x 64
+  if (tile_b != TILE_64x64 || (tile_a != TILE_64x128 && tile_a != TILE_64x64)) return hipErrorInvalidValue;
+  int bm, bn;
+  tile_dims(tile_a, bm, bn);
+  a.tiles_m = (a.M + bm - 1) / bm;
+  a.tiles_n = (a.N + bn - 1) / bn;
+  b.tiles_m = (b.M + 63) / 64;
+  b.tiles_n = (b.N + 63) / 64;
+  const long long ga = (long long)a.tiles_m * a.tiles_n * a.splits;
+  const long long gb = (long long)b.tiles_m * b.tiles_n * b.splits;
+  if (ga <= 0 || gb <= 0 || ga + gb > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(ga + gb));
+  if (tile_a == TILE_64x128)
+    hipLaunchKernelGGL((dual_gemm_kernel<A128, B64>), grid, dim3(256), 0, s, a, b, (int)ga);
+  else
+    hipLaunchKernelGGL((dual_gemm_kernel<A64, B64>), grid, dim3(256), 0, s, a, b, (int)ga);
+  return hipGetLastError();
 }
 
 hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,

@@ -303,7 +303,19 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   const int t_begin = slice * per_slice;
   const int t_end = (t_begin + per_slice < n_tiles) ? t_begin + per_slice : n_tiles;
   const int my_tiles = t_end - t_begin;
-  if (my_tiles <= 0) return;  // uniform over the work-group
+  // The reduction this launch carries along goes to the work-groups with the least tile
+  // work: those of the slices that got fewer tiles than the rest (often none at all, when
+  // the tiles do not divide over the slices), or to everybody when all slices are equal.
+  const bool has_tail = p.tail.n + p.tail.n2 > 0;
+  const int first_light = n_tiles / per_slice;           // slices below this one are full
+  const int n_light = p.n_slices - first_light;
+  const bool tail_here = has_tail && (n_light == 0 || slice >= first_light);
+  const int tail_rank = n_light == 0 ? wg : tile_m * n_light + (slice - first_light);
+  const int tail_ranks = p.tiles_m * (n_light == 0 ? p.n_slices : n_light);
+  if (my_tiles <= 0) {  // uniform over the work-group
+    if (tail_here) reduce_splits_part(p.tail, tail_rank, tail_ranks, tid);
+    return;
+  }
 
   const bf16* __restrict__ B2 = static_cast<const bf16*>(p.B2);
   uint4 rb0[TB2::PIECES], rb1[TB2::PIECES];
@@ -332,6 +344,9 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   };
   uint2 bv0[4], bv1[4];
   load_bias(bv0, 0);
+
+  // this work-group's share of the carried reduction, while its own first loads are in flight
+  if (tail_here) reduce_splits_part(p.tail, tail_rank, tail_ranks, tid);
 
   // ---------------- the intermediate tile Zt -> LDS ----------------
   if (FUSED) {

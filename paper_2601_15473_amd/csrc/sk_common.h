@@ -52,6 +52,48 @@ struct ReduceArgs {
   float scale, scale2;
 };
 
+// One segment of a split reduction, the part that falls to work-group `block` of `nblocks`
+// (256 threads each): 16-byte pieces are dealt round-robin, four per thread and pass so
+// that their loads overlap; every piece sums its slabs in index order.
+__device__ __forceinline__ void reduce_segment_part(const float* __restrict__ part, float* __restrict__ out,
+                                                    int64_t n, int splits, float scale, int block,
+                                                    int nblocks, int tid) {
+  constexpr int U = 4;
+  const int64_t pieces = n / 4, stride = (int64_t)nblocks * 256;
+  for (int64_t q0 = (int64_t)block * 256 + tid; q0 < pieces; q0 += stride * U) {
+    float4 s[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * stride;
+      s[u] = q < pieces ? *reinterpret_cast<const float4*>(part + q * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll 8
+    for (int k = 1; k < splits; ++k) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t q = q0 + u * stride;
+        if (q < pieces) {
+          const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + q * 4);
+          s[u].x += v.x; s[u].y += v.y; s[u].z += v.z; s[u].w += v.w;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * stride;
+      if (q < pieces)
+        *reinterpret_cast<float4*>(out + q * 4) =
+            make_float4(s[u].x * scale, s[u].y * scale, s[u].z * scale, s[u].w * scale);
+    }
+  }
+}
+
+// Both segments of a split reduction (see ReduceArgs), this work-group's part.
+__device__ __forceinline__ void reduce_splits_part(const ReduceArgs& p, int block, int nblocks, int tid) {
+  if (p.n > 0) reduce_segment_part(p.part, p.out, p.n, p.splits, p.scale, block, nblocks, tid);
+  if (p.n2 > 0) reduce_segment_part(p.part2, p.out2, p.n2, p.splits2, p.scale2, block, nblocks, tid);
+}
+
 // XCD-aware work-group order.  Work-groups are handed to the 8 XCDs round-robin,
 // so consecutive hardware ids land on different L2s.  Remap so that each XCD
 // gets one contiguous run of logical tile ids (neighbouring tiles share operand

@@ -36,10 +36,16 @@ class DeviceLayer:
         self.dU = torch.full((w.R, w.d_out), fill, dtype=torch.float32, device="cuda")
         self.db = torch.full((w.d_out,), fill, dtype=torch.float32, device="cuda")
         self.args = (w.tokens, w.d_in, w.d_out, w.l, w.k, self.dt)
-        need = max(libsk.sk_linear_workspace_bytes(op, *self.args) for op in (0, 1, 2))
+        need = max(libsk.sk_linear_workspace_bytes(op, *self.args) for op in (0, 1, 2, 4))
         assert need != 2 ** 64 - 1
         self.ws_bytes = need
         self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+    def bwd(self, stream=None, with_db=True):
+        """Both gradients in one call (sk_linear_bwd)."""
+        return self.sk.sk_linear_bwd(self.x, self.dY, self.S_cat, self.U_cat, self.dX, self.dU,
+                                     self.db if with_db else None, *self.args,
+                                     self.ws, self.ws_bytes, stream)
 
     def fwd(self, stream=None):
         return self.sk.sk_linear_fwd(self.x, self.S_cat, self.U_cat, self.b, self.y, *self.args,

@@ -172,6 +172,49 @@ def test_outputs_past_two_gib_sampled(sk):
     assert not torch.isnan(dev.y[100000:].float().sum())
 
 
+BWD_CASES = [
+    W.scaled(W.BERT_BASE_FFN_UP, tokens=1000),        # shared launches (R = 128, long first contraction)
+    W.BERT_BASE_FFN_UP,
+    W.scaled(W.BERT_BASE_PROJ[0], tokens=700),        # R = 32: 64 x 64 tiles
+    W.BERT_BASE_PROJ[2],
+    W.Workload("bf16_ragged", 333, 208, 176, 3, 16, "bf16", seed=4),
+    W.Workload("bf16_one_token", 1, 64, 48, 1, 16, "bf16", seed=3),
+    W.scaled(W.BERT_LARGE_FFN_UP, tokens=600),        # wide sketch: the two gradients one after the other
+    W.Workload("f32_ragged", 77, 48, 80, 3, 16, "f32", seed=1),
+]
+
+
+@pytest.mark.parametrize("w", BWD_CASES, ids=lambda w: f"{w.name}_T{w.tokens}")
+def test_single_call_backward(sk, w):
+    """sk_linear_bwd against the oracle, and against the two separate calls: dU and db bit
+    for bit, dX to the tolerance (its fp32 partial sums may be ordered differently)."""
+    print(f"case bwd {w.name} T={w.tokens} in={w.d_in} out={w.d_out} l={w.l} k={w.k} {w.dtype}", flush=True)
+    sk.sk_set_plan(0)
+    t = W.generate(w)
+    dev = DeviceLayer(t, sk)
+    sk.check(dev.bwd())
+    torch.cuda.synchronize()
+    want = oracle_all(t)
+    got = dict(dX=to_f64(dev.dX), dU=to_f64(dev.dU), db=to_f64(dev.db))
+    errs = {n: rel_err(got[n], want[n]) for n in got}
+    print("   errors:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= TOL[w.dtype], (n, e)
+    sep = DeviceLayer(t, sk)
+    sk.check(sep.bwd_input())
+    sk.check(sep.bwd_weight())
+    torch.cuda.synchronize()
+    assert torch.equal(dev.dU.view(torch.int32), sep.dU.view(torch.int32))
+    assert torch.equal(dev.db.view(torch.int32), sep.db.view(torch.int32))
+    assert rel_err(to_f64(dev.dX), to_f64(sep.dX)) <= TOL[w.dtype]
+    # no bias gradient wanted
+    nob = DeviceLayer(t, sk)
+    sk.check(nob.bwd(with_db=False))
+    torch.cuda.synchronize()
+    assert torch.isnan(nob.db).all()
+    assert torch.equal(nob.dU.view(torch.int32), sep.dU.view(torch.int32))
+
+
 def test_forced_big_tiles(sk, monkeypatch):
     """The large-shape code paths (big tiles, the bias gradient from its own kernel)
     on a shape small enough for a full oracle pass."""
