@@ -510,60 +510,83 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
   unsigned char* ws_in = static_cast<unsigned char*>(workspace);
   unsigned char* ws_w = ws_in + in_bytes;
 
-  // The shared-launch schedule needs the shapes the narrow-sketch plans produce: the input
-  // gradient as split-K slabs + expand, Z^T on the 64 x 64 tile, split token contraction
-  // with the column sums riding on it.
-  const SketchPlan q = plan_sketch(s, out);
+  // Shared-launch schedules exist for the shapes the automatic plans produce on the
+  // benchmark configurations (bf16; the dual kernel is built for a few tile pairs only);
+  // everything else runs the two gradients one after the other.
   const WeightPlan w = plan_weight(s);
-  const int z_tile = s.dtype == SK_BF16 ? choose_tile(s.R, tokens, in, 1) : -1;
-  const bool shared = s.dtype == SK_BF16 && chain_supported(s.R) && s.R <= 128 &&
-                      g_plan.load(std::memory_order_relaxed) == PLAN_AUTO && q.splits > 1 &&
-                      (q.tile == TILE_64x128 || q.tile == TILE_64x64) && z_tile == TILE_64x64 &&
-                      !w.own_colsum && w.splits > 1;
-  if (!shared) {
-    const sk_status a = sk_linear_bwd_input(dY, S_cat, U_cat, dX, tokens, in, out, l, k, dtype, ws_in,
-                                            in_bytes, stream);
-    if (a != SK_OK) return a;
-    return sk_linear_bwd_weight(x, S_cat, dY, dU_cat, dbias, tokens, in, out, l, k, dtype, ws_w, w_bytes,
-                                stream);
-  }
+  const bool bf16_auto = s.dtype == SK_BF16 && g_plan.load(std::memory_order_relaxed) == PLAN_AUTO &&
+                         !w.own_colsum;
+  const Plan in_plan = pick_plan(s, SK_OP_BWD_INPUT);
+  const int z_tile = bf16_auto ? choose_tile(s.R, tokens, in, 1) : -1;
+  const GemmKind du_kind = GEMM_NN_F32_COLSUM;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const float scale = 1.0f / (float)l;
-  g_hip_error.clear();
 
-  // launch 1: G slabs = dY . U_cat^T (split over `out`)  beside  Z^T = S_cat^T . x^T
-  GemmArgs g = dense_args(dY, out, U_cat, out, ws_in, s.R, tokens, s.R, out, 1.0f, nullptr);
-  g.splits = q.splits; g.k_per_split = q.k_per_split;
   void* Z = ws_w;
   float* part = reinterpret_cast<float*>(ws_w + w.z_bytes);
   float* cpart = reinterpret_cast<float*>(ws_w + w.z_bytes + w.part_bytes);
+  // Z^T = S_cat^T . x^T (zero-filled row padding)
   GemmArgs z = dense_args(S_cat, s.R, x, in, Z, w.ldz, s.R, tokens, in, 1.0f, nullptr);
   z.n_store = (int)w.ldz;
-  hipError_t e = launch_dual_gemm_bf16(q.tile, g, z_tile, z, hs);
-  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (dY.U^T beside x.S)");
+  // dU (or its slabs) = Z^T . dY with the column sums of dY, the token axis split in order
+  GemmArgs du{};
+  du.A = Z; du.lda = w.ldz;
+  du.B = dY; du.ldb = out; du.ldc = out;
+  du.M = s.R; du.N = (int)out; du.K = (int)tokens;
+  du.splits = w.splits; du.k_per_split = w.k_per_split;
+  if (w.splits == 1) { du.C = dU_cat; du.colsum = dbias; du.scale = scale; }
+  else { du.C = part; du.colsum = dbias ? cpart : nullptr; du.scale = 1.0f; }
+  ReduceArgs red{};
+  red.part = part; red.out = dU_cat; red.n = w.splits > 1 ? (int64_t)s.R * out : 0; red.scale = scale;
+  red.part2 = cpart; red.out2 = dbias; red.n2 = (dbias && w.colsum_splits > 1) ? out : 0; red.scale2 = 1.0f;
+  red.splits = w.splits; red.splits2 = w.colsum_splits;
 
-  // launch 2: dU slabs = Z^T . dY with the column sums of dY, the token axis split in order
-  GemmArgs a{};
-  a.A = Z; a.lda = w.ldz;
-  a.B = dY; a.ldb = out; a.ldc = out;
-  a.M = s.R; a.N = (int)out; a.K = (int)tokens;
-  a.splits = w.splits; a.k_per_split = w.k_per_split;
-  a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
-  e = launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs);
-  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (Z^T.dY)");
+  // --- narrow sketch: split-K slabs of G beside Z^T | Z^T.dY | expand dX, carrying the sums ---
+  const SketchPlan q = plan_sketch(s, out);
+  if (bf16_auto && chain_supported(s.R) && s.R <= 128 && q.splits > 1 && w.splits > 1 &&
+      dual_gemm_supported(GEMM_NT_F32, q.tile, GEMM_TT, z_tile)) {
+    g_hip_error.clear();
+    GemmArgs g = dense_args(dY, out, U_cat, out, ws_in, s.R, tokens, s.R, out, 1.0f, nullptr);
+    g.splits = q.splits; g.k_per_split = q.k_per_split;
+    hipError_t e = launch_dual_gemm_bf16(GEMM_NT_F32, q.tile, g, GEMM_TT, z_tile, z, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (dY.U^T beside x.S)");
+    e = launch_gemm_bf16(du_kind, w.tile, du, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (Z^T.dY)");
+    ChainArgs c{};
+    c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
+    c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
+    c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
+    c.n_slices = chain_slices(tokens, in, s.R);
+    c.Z = ws_in; c.z_splits = q.splits; c.z_slab = (int64_t)tokens * s.R;
+    c.tail = red;
+    e = launch_chain_bf16(true, false, c, hs);
+    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd (expand + sum of splits)");
+  }
 
-  // launch 3: dX = scale * (sum of G slabs) . S_cat^T, carrying the sum of the dU and db slabs
-  ChainArgs c{};
-  c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
-  c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
-  c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-  c.n_slices = chain_slices(tokens, in, s.R);
-  c.Z = ws_in; c.z_splits = q.splits; c.z_slab = (int64_t)tokens * s.R;
-  c.tail.part = part; c.tail.out = dU_cat; c.tail.n = (int64_t)s.R * out; c.tail.scale = scale;
-  c.tail.part2 = cpart; c.tail.out2 = dbias; c.tail.n2 = dbias ? out : 0; c.tail.scale2 = 1.0f;
-  c.tail.splits = w.splits; c.tail.splits2 = w.colsum_splits;
-  e = launch_chain_bf16(true, false, c, hs);
-  return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd (expand + sum of splits)");
+  // --- wide sketch (two GEMMs per gradient): dY.U^T beside Z^T | Z^T.dY beside G.S^T | sums ---
+  const int g_tile = bf16_auto ? choose_tile(tokens, s.R, out, 1) : -1;
+  const int dx_tile = bf16_auto ? choose_tile(tokens, in, s.R, 1) : -1;
+  if (bf16_auto && in_plan == PLAN_TWO_GEMM && dual_gemm_supported(GEMM_NT, g_tile, GEMM_TT, z_tile) &&
+      dual_gemm_supported(du_kind, w.tile, GEMM_NT, dx_tile)) {
+    g_hip_error.clear();
+    const GemmArgs g = dense_args(dY, out, U_cat, out, ws_in, s.R, tokens, s.R, out, 1.0f, nullptr);
+    hipError_t e = launch_dual_gemm_bf16(GEMM_NT, g_tile, g, GEMM_TT, z_tile, z, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (dY.U^T beside x.S)");
+    const GemmArgs dx = dense_args(ws_in, s.R, S_cat, s.R, dX, in, tokens, in, s.R, scale, nullptr);
+    e = launch_dual_gemm_bf16(du_kind, w.tile, du, GEMM_NT, dx_tile, dx, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (Z^T.dY beside G.S^T)");
+    if (red.n + red.n2 > 0) {
+      e = launch_reduce_splits(red, hs);
+      if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (sum of splits)");
+    }
+    return SK_OK;
+  }
+
+  const sk_status a = sk_linear_bwd_input(dY, S_cat, U_cat, dX, tokens, in, out, l, k, dtype, ws_in,
+                                          in_bytes, stream);
+  if (a != SK_OK) return a;
+  return sk_linear_bwd_weight(x, S_cat, dY, dU_cat, dbias, tokens, in, out, l, k, dtype, ws_w, w_bytes,
+                              stream);
 }
 
 sk_status sk_linear_bwd_weight_first(const void* x, const void* U_cat, const void* dY, float* dA,

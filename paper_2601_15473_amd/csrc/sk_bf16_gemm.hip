@@ -435,25 +435,57 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* 
   }
 }
 
-hipError_t launch_dual_gemm_bf16(int tile_a, GemmArgs a, int tile_b, GemmArgs b, hipStream_t s) {
-  typedef GemmTile<64, 128, 2, 2, true, true, float, false, 2> A128;   // GEMM_NT_F32, 64 x 128
-  typedef GemmTile<64, 64, 2, 2, true, true, float, false, 2> A64;     // GEMM_NT_F32, 64 x 64
-  typedef GemmTile<64, 64, 2, 2, false, true, bf16, false, 2> B64;     // GEMM_TT, 64 x 64
-  if (tile_b != TILE_64x64 || (tile_a != TILE_64x128 && tile_a != TILE_64x64)) return hipErrorInvalidValue;
+namespace {
+// The pairs of (kind, tile) the dual kernel is built for: the ones the backward pass's
+// plans produce on the benchmark shapes.  `first` should be the longer-running GEMM: its
+// work-groups are dispatched first and the other's fill in beside them.
+struct DualPair { GemmKind ka; int ta; GemmKind kb; int tb; };
+const DualPair kDualPairs[] = {
+    {GEMM_NT_F32, TILE_64x128, GEMM_TT, TILE_64x64},           // narrow sketch, R in 65..128
+    {GEMM_NT_F32, TILE_64x64, GEMM_TT, TILE_64x64},            // narrow sketch, R <= 64
+    {GEMM_NT, TILE_128x128, GEMM_TT, TILE_128x128},            // wide sketch: dY.U^T beside Z^T
+    {GEMM_NN_F32_COLSUM, TILE_128x64, GEMM_NT, TILE_128x128},  // wide sketch: Z^T.dY beside G.S^T
+};
+int dual_pair_index(GemmKind ka, int ta, GemmKind kb, int tb) {
+  for (int i = 0; i < (int)(sizeof(kDualPairs) / sizeof(kDualPairs[0])); ++i)
+    if (kDualPairs[i].ka == ka && kDualPairs[i].ta == ta && kDualPairs[i].kb == kb && kDualPairs[i].tb == tb)
+      return i;
+  return -1;
+}
+}  // namespace
+
+bool dual_gemm_supported(GemmKind kind_a, int tile_a, GemmKind kind_b, int tile_b) {
+  return dual_pair_index(kind_a, tile_a, kind_b, tile_b) >= 0;
+}
+
+hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKind kind_b, int tile_b,
+                                 GemmArgs b, hipStream_t s) {
+  const int pair = dual_pair_index(kind_a, tile_a, kind_b, tile_b);
+  if (pair < 0) return hipErrorInvalidValue;
   int bm, bn;
   tile_dims(tile_a, bm, bn);
   a.tiles_m = (a.M + bm - 1) / bm;
   a.tiles_n = (a.N + bn - 1) / bn;
-  b.tiles_m = (b.M + 63) / 64;
-  b.tiles_n = (b.N + 63) / 64;
+  tile_dims(tile_b, bm, bn);
+  b.tiles_m = (b.M + bm - 1) / bm;
+  b.tiles_n = (b.N + bn - 1) / bn;
   const long long ga = (long long)a.tiles_m * a.tiles_n * a.splits;
   const long long gb = (long long)b.tiles_m * b.tiles_n * b.splits;
   if (ga <= 0 || gb <= 0 || ga + gb > 0x7fffffffLL) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)(ga + gb));
-  if (tile_a == TILE_64x128)
-    hipLaunchKernelGGL((dual_gemm_kernel<A128, B64>), grid, dim3(256), 0, s, a, b, (int)ga);
-  else
-    hipLaunchKernelGGL((dual_gemm_kernel<A64, B64>), grid, dim3(256), 0, s, a, b, (int)ga);
+  const dim3 grid((unsigned)(ga + gb)), block(256);
+  typedef GemmTile<64, 128, 2, 2, true, true, float, false, 2> NTF_64x128;
+  typedef GemmTile<64, 64, 2, 2, true, true, float, false, 2> NTF_64x64;
+  typedef GemmTile<64, 64, 2, 2, false, true, bf16, false, 2> TT_64x64;
+  typedef GemmTile<128, 128, 2, 2, true, true, bf16, false, 2> NT_128x128;
+  typedef GemmTile<128, 128, 2, 2, false, true, bf16, false, 2> TT_128x128;
+  typedef GemmTile<128, 64, 2, 2, true, false, float, true, 2> NNFC_128x64;
+  switch (pair) {
+    case 0: hipLaunchKernelGGL((dual_gemm_kernel<NTF_64x128, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
+    case 1: hipLaunchKernelGGL((dual_gemm_kernel<NTF_64x64, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
+    case 2: hipLaunchKernelGGL((dual_gemm_kernel<NT_128x128, TT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
+    case 3: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x64, NT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

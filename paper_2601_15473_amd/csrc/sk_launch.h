@@ -41,10 +41,12 @@ hipError_t launch_gemm_f32(GemmKind kind, const GemmArgs& a, hipStream_t s);
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16;
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s);
-// Two GEMMs that do not depend on each other in one launch (see dual_gemm_kernel).
-// Supported pairs: `a` a split-K NT GEMM into fp32 slabs on a 64 x 128 or 64 x 64 tile,
-// `b` a TT GEMM into the storage type on a 64 x 64 tile; anything else is invalid.
-hipError_t launch_dual_gemm_bf16(int tile_a, GemmArgs a, int tile_b, GemmArgs b, hipStream_t s);
+// Two GEMMs that do not depend on each other in one launch (see dual_gemm_kernel); built
+// for a few (kind, tile) pairs only -- ask dual_gemm_supported first.  `a` should be the
+// longer-running one.
+bool dual_gemm_supported(GemmKind kind_a, int tile_a, GemmKind kind_b, int tile_b);
+hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKind kind_b, int tile_b,
+                                 GemmArgs b, hipStream_t s);
 // fp32 column sums of the dense row-major bf16 matrix in [rows, cols], one output row of
 // `cols` sums per run of rows_per_split rows (splits runs)
 hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,

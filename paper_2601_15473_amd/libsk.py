@@ -13,6 +13,15 @@ from __future__ import annotations
 import ctypes
 import os
 
+# Load order matters: PyTorch ships its own copy of the HIP runtime under the same soname
+# as the system's, and a process can hold only one of them.  The runtime that owns the
+# tensors' memory and streams must be the one libsk's launches go through, so torch (when
+# it is installed) is imported before libsk.so pulls in a runtime of its own.
+try:
+    import torch  # noqa: F401
+except ImportError:   # plain-pointer callers without PyTorch
+    pass
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libsk.so")
 

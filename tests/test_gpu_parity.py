@@ -179,7 +179,10 @@ BWD_CASES = [
     W.BERT_BASE_PROJ[2],
     W.Workload("bf16_ragged", 333, 208, 176, 3, 16, "bf16", seed=4),
     W.Workload("bf16_one_token", 1, 64, 48, 1, 16, "bf16", seed=3),
-    W.scaled(W.BERT_LARGE_FFN_UP, tokens=600),        # wide sketch: the two gradients one after the other
+    W.scaled(W.BERT_LARGE_FFN_UP, tokens=600),        # wide sketch, too few tokens for the shared launches
+    W.scaled(W.BERT_LARGE_FFN_UP, tokens=5000),       # wide sketch: shared launches (128 x 128 tiles)
+    W.scaled(W.BERT_LARGE_FFN_DOWN, tokens=4100),     # ... with a split token contraction
+    W.scaled(W.BERT_BASE_PROJ[3], tokens=700),        # R = 256: no shared schedule for its tiles
     W.Workload("f32_ragged", 77, 48, 80, 3, 16, "f32", seed=1),
 ]
 
