@@ -99,7 +99,7 @@ TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tuna
   if (dtype == SK_BF16) {
     w.tile = M > 64 ? TILE_128x64 : TILE_64x64;
     if (((M + 255) / 256) * ((N + 255) / 256) >= NUM_CUS) w.tile = TILE_256x256_W8;
-    else if (((M + 127) / 128) * ((N + 127) / 128) >= NUM_CUS) w.tile = TILE_128x128;
+    else if (((M + 127) / 128) * ((N + 127) / 128) >= NUM_CUS / 2) w.tile = TILE_128x128;  // measured: from half a chip of tiles on, 128 x 128 beats 128 x 64
     if (const char* e = tunable ? getenv("SK_TUNE_WTILE") : nullptr) w.tile = atoi(e);  // tuning experiments only
     w.big_tile = w.tile == TILE_256x256_W8 || w.tile == TILE_256x256;
     tile_dims(w.tile, bm, bn);
