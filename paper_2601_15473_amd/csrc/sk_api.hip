@@ -550,14 +550,15 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
     g.splits = q.splits; g.k_per_split = q.k_per_split;
     hipError_t e = launch_dual_gemm_bf16(GEMM_NT_F32, q.tile, g, GEMM_TT, z_tile, z, hs);
     if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (dY.U^T beside x.S)");
-    e = launch_gemm_bf16(du_kind, w.tile, du, hs);
-    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (Z^T.dY)");
     ChainArgs c{};
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
     c.n_slices = chain_slices(tokens, in, s.R);
     c.Z = ws_in; c.z_splits = q.splits; c.z_slab = (int64_t)tokens * s.R;
+    // Z^T.dY, then the expansion of dX carrying the sum of the token splits
+    e = launch_gemm_bf16(du_kind, w.tile, du, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (Z^T.dY)");
     c.tail = red;
     e = launch_chain_bf16(true, false, c, hs);
     return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd (expand + sum of splits)");
