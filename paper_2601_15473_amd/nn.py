@@ -4,9 +4,10 @@ paper's "Tool Usage" section: the layer averages ``num_terms`` sketched products
 whose sketches have rank ``low_rank``), with autograd support.
 
 Everything that computes runs in libsk's HIP kernels: ``forward`` calls
-``sk_linear_fwd``; ``backward`` calls ``sk_linear_bwd_input`` and
-``sk_linear_bwd_weight`` (which recomputes x.S rather than keeping it from the
-forward pass).  PyTorch provides the tensors, the stream and the autograd graph.
+``sk_linear_fwd``; ``backward`` calls ``sk_linear_bwd`` (both gradients in one
+call) or, when only one of them is wanted, ``sk_linear_bwd_input`` or
+``sk_linear_bwd_weight``; the factor gradient recomputes x.S rather than keeping
+it from the forward pass.  PyTorch provides the tensors, the stream and the autograd graph.
 There is no CPU path: tensors that are not on a GPU raise.
 
     y = (1/l) * sum_i (x . S_i) . U_i + b        S_i fixed random, U_i and b learned
@@ -85,17 +86,25 @@ class SKLinearFunction(torch.autograd.Function):
         dX = dU = db = None
         with torch.cuda.device(dY.device):
             stream = torch.cuda.current_stream().cuda_stream
+            want_w = need_du or (need_db and ctx.has_bias)
             need = max(sk.sk_linear_workspace_bytes(op, *ctx.args)
-                       for op in (sk.SK_OP_BWD_INPUT, sk.SK_OP_BWD_WEIGHT))
+                       for op in (sk.SK_OP_BWD_INPUT, sk.SK_OP_BWD_WEIGHT, sk.SK_OP_BWD))
             ws = _workspace(dY.device, stream, need)
             if need_dx:
                 dX = torch.empty((tokens, d_in), dtype=dtype, device=dY.device)
-                sk.check(sk.sk_linear_bwd_input(dY2, S_cat, U_cat, dX, *ctx.args, ws, ws.numel(), stream))
-                dX = dX.reshape(ctx.x_shape)
-            if need_du or (need_db and ctx.has_bias):
+            if want_w:
                 dU32 = torch.empty((l * k, d_out), dtype=torch.float32, device=dY.device)
                 db32 = torch.empty((d_out,), dtype=torch.float32, device=dY.device) if ctx.has_bias else None
+            if need_dx and want_w:      # both gradients from one call (its kernels share launches)
+                sk.check(sk.sk_linear_bwd(x2, dY2, S_cat, U_cat, dX, dU32, db32, *ctx.args,
+                                          ws, ws.numel(), stream))
+            elif need_dx:
+                sk.check(sk.sk_linear_bwd_input(dY2, S_cat, U_cat, dX, *ctx.args, ws, ws.numel(), stream))
+            elif want_w:
                 sk.check(sk.sk_linear_bwd_weight(x2, S_cat, dY2, dU32, db32, *ctx.args, ws, ws.numel(), stream))
+            if need_dx:
+                dX = dX.reshape(ctx.x_shape)
+            if want_w:
                 dU = dU32.to(dtype) if need_du else None
                 db = db32.to(dtype) if (need_db and ctx.has_bias) else None
         return dX, None, dU, db, None, None
