@@ -56,7 +56,10 @@ sk_status check_shape(int64_t tokens, int64_t in, int64_t out, int32_t l, int32_
 // every CU a work-group without being mostly padding, the smallest when the problem
 // cannot fill the chip.
 int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
-  if (const char* e = getenv("SK_TUNE_TILE")) return atoi(e);  // tuning experiments only
+  if (const char* e = getenv("SK_TUNE_TILE")) {  // tuning experiments only
+    const int t = atoi(e);
+    if (t >= 0 && t < TILE_COUNT) return t;
+  }
   const int64_t m_cap = (M + 63) / 64 * 64, n_cap = (N + 63) / 64 * 64;
   static const int order[] = {TILE_256x256_W8, TILE_128x128, TILE_128x64, TILE_64x128, TILE_64x64};
   for (int i = 0; i < (int)(sizeof(order) / sizeof(order[0])); ++i) {
@@ -100,7 +103,10 @@ TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tuna
     w.tile = M > 64 ? TILE_128x64 : TILE_64x64;
     if (((M + 255) / 256) * ((N + 255) / 256) >= NUM_CUS) w.tile = TILE_256x256_W8;
     else if (((M + 127) / 128) * ((N + 127) / 128) >= NUM_CUS / 2) w.tile = TILE_128x128;  // measured: from half a chip of tiles on, 128 x 128 beats 128 x 64
-    if (const char* e = tunable ? getenv("SK_TUNE_WTILE") : nullptr) w.tile = atoi(e);  // tuning experiments only
+    if (const char* e = tunable ? getenv("SK_TUNE_WTILE") : nullptr) {  // tuning experiments only
+      const int t = atoi(e);
+      if (t >= 0 && t < TILE_COUNT) w.tile = t;
+    }
     w.big_tile = w.tile == TILE_256x256_W8 || w.tile == TILE_256x256;
     tile_dims(w.tile, bm, bn);
   } else {
@@ -129,7 +135,7 @@ TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tuna
     if (best < 0.0 || t < best) { best = t; splits = sp_eff; kps = k; }
   }
   if (const char* e = tunable ? getenv("SK_TUNE_WSPLITS") : nullptr) {  // tuning experiments only
-    splits = atoi(e);
+    splits = atoi(e) < 1 ? 1 : (atoi(e) > max_splits ? max_splits : atoi(e));
     kps = ((T + splits - 1) / splits + 63) / 64 * 64;
     splits = (T + kps - 1) / kps;
   }
@@ -239,7 +245,7 @@ int chain_slices(int64_t T, int64_t N, int R) {
   const int64_t tiles_m = (T + 63) / 64;
   const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
   int64_t sl = NUM_CUS / tiles_m;
-  if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only
+  if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
   return (int)sl;
