@@ -446,6 +446,8 @@ const DualPair kDualPairs[] = {
     {GEMM_NT, TILE_128x128, GEMM_TT, TILE_128x128},            // wide sketch: dY.U^T beside Z^T
     {GEMM_NN_F32_COLSUM, TILE_128x64, GEMM_NT, TILE_128x128},  // wide sketch: Z^T.dY beside G.S^T
     {GEMM_NN_F32_COLSUM, TILE_128x128, GEMM_NT, TILE_128x128},
+    {GEMM_NT, TILE_64x64, GEMM_TT, TILE_64x64},                // R = 256..384 at BERT-base width
+    {GEMM_NN_F32_COLSUM, TILE_128x64, GEMM_NT, TILE_128x64},
 };
 int dual_pair_index(GemmKind ka, int ta, GemmKind kb, int tb) {
   for (int i = 0; i < (int)(sizeof(kDualPairs) / sizeof(kDualPairs[0])); ++i)
@@ -481,12 +483,16 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
   typedef GemmTile<128, 128, 2, 2, false, true, bf16, false, 2> TT_128x128;
   typedef GemmTile<128, 64, 2, 2, true, false, float, true, 2> NNFC_128x64;
   typedef GemmTile<128, 128, 2, 2, true, false, float, true, 2> NNFC_128x128;
+  typedef GemmTile<64, 64, 2, 2, true, true, bf16, false, 2> NT_64x64;
+  typedef GemmTile<128, 64, 2, 2, true, true, bf16, false, 2> NT_128x64;
   switch (pair) {
     case 0: hipLaunchKernelGGL((dual_gemm_kernel<NTF_64x128, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
     case 1: hipLaunchKernelGGL((dual_gemm_kernel<NTF_64x64, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
     case 2: hipLaunchKernelGGL((dual_gemm_kernel<NT_128x128, TT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
     case 3: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x64, NT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
     case 4: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x128, NT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
+    case 5: hipLaunchKernelGGL((dual_gemm_kernel<NT_64x64, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
+    case 6: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x64, NT_128x64>), grid, block, 0, s, a, b, (int)ga); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

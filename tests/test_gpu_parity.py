@@ -182,7 +182,9 @@ BWD_CASES = [
     W.scaled(W.BERT_LARGE_FFN_UP, tokens=600),        # wide sketch, too few tokens for the shared launches
     W.scaled(W.BERT_LARGE_FFN_UP, tokens=5000),       # wide sketch: shared launches (128 x 128 tiles)
     W.scaled(W.BERT_LARGE_FFN_DOWN, tokens=4100),     # ... with a split token contraction
-    W.scaled(W.BERT_BASE_PROJ[3], tokens=700),        # R = 256: no shared schedule for its tiles
+    W.scaled(W.BERT_BASE_PROJ[3], tokens=700),        # R = 256, too few tokens for the shared launches
+    W.BERT_BASE_PROJ[3],                              # R = 256: shared launches on 64 x 64 / 128 x 64 tiles
+    W.BERT_BASE_PROJ[4],                              # R = 384
     W.Workload("f32_ragged", 77, 48, 80, 3, 16, "f32", seed=1),
 ]
 
