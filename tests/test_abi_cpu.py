@@ -105,3 +105,18 @@ def test_first_stage_gradient_argument_checks():
     assert 0 < need < 2 ** 63
     assert f(P, P, P, P, T, i, o, l, k, 0, R, dt, P, need - 1) == sk.SK_ERR_WORKSPACE
     assert f(P, P, P, P, T, i, o, l, k, 0, R, dt, None, 0) == sk.SK_ERR_WORKSPACE
+
+
+def test_single_call_backward_argument_checks_and_workspace():
+    f = sk.sk_linear_bwd
+    big = 1 << 30
+    assert f(None, P, P, P, P, P, P, *ARGS, P, big) == sk.SK_ERR_INVALID_ARG
+    assert f(P, P, P, P, P + 8, P, P, *ARGS, P, big) == sk.SK_ERR_INVALID_ARG
+    assert f(P, P, P, P, P, P, None, 64, 64, 60, 1, 16, sk.SK_BF16, P, big) == sk.SK_ERR_UNSUPPORTED
+    for a in (ARGS, (4096, 768, 3072, 2, 64, sk.SK_BF16), (8192, 1024, 4096, 4, 128, sk.SK_BF16),
+              (300, 48, 80, 3, 16, sk.SK_F32)):
+        both = sk.sk_linear_workspace_bytes(sk.SK_OP_BWD, *a)
+        parts = (sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_INPUT, *a) +
+                 sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT, *a))
+        assert both == parts            # the two gradients' buffers side by side
+        assert f(P, P, P, P, P, P, None, *a, P, both - 1) == sk.SK_ERR_WORKSPACE
