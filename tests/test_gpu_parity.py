@@ -88,8 +88,8 @@ def test_no_bias_and_no_dbias(sk, plan):
 
 
 # Full benchmark sizes, in the automatic plan the benchmark times.
-@pytest.mark.parametrize("w", [W.BERT_BASE_FFN_UP, W.BERT_BASE_PROJ[2], W.BERT_BASE_PROJ[4],
-                               W.BERT_LARGE_FFN_UP, W.BERT_LARGE_FFN_DOWN], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", (W.BERT_BASE_FFN_UP,) + W.BERT_BASE_PROJ +
+                         (W.BERT_LARGE_FFN_UP, W.BERT_LARGE_FFN_DOWN), ids=lambda w: w.name)
 def test_parity_full_size(sk, w):
     check_all(sk, w, 0)
 
