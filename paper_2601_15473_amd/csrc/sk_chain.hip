@@ -272,10 +272,7 @@ struct SmallLds {
   typedef OpTile<RT, B1_KC> TB1;
   static constexpr int Z_LD = RT + 8;
   static constexpr int Z_BYTES = CH_BM * Z_LD * 2;
-  static constexpr int OUT_LD = CS_BN * 2 + 8;
-  static constexpr int OUT_BYTES = CH_BM * OUT_LD;
-  // Zt is dead once every wave has lifted it into registers: the output staging reuses it
-  static constexpr int HEAD_BYTES = Z_BYTES > OUT_BYTES ? Z_BYTES : OUT_BYTES;
+  static constexpr int HEAD_BYTES = Z_BYTES;
   static constexpr int S2_BYTES = 2 * TB2::ELEMS * 2;
   static constexpr int S1_BYTES = FUSED ? 2 * (TA::ELEMS + TB1::ELEMS) * 2 : 0;
   static constexpr int BYTES = HEAD_BYTES + (S1_BYTES > S2_BYTES ? S1_BYTES : S2_BYTES);
@@ -288,7 +285,6 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   constexpr int KS = RT / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[L::BYTES];
   bf16* const Zs = reinterpret_cast<bf16*>(smem);
-  unsigned char* const ostage = smem;
   unsigned char* const work = smem + L::HEAD_BYTES;
   bf16* const Bbuf = reinterpret_cast<bf16*>(work);
 
@@ -489,7 +485,7 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
     for (int ks = 0; ks < KS; ++ks) fa[i][ks] = read_frag_rowmajor<L::Z_LD>(Zs, i * 32, ks, lane);
 
   TB2::store(Bbuf, rb0, tid);
-  __syncthreads();  // also: every wave is done reading Zt, whose space the output staging reuses
+  __syncthreads();
 
   bf16* __restrict__ C = static_cast<bf16*>(p.C);
   const float scale = p.scale;
@@ -505,34 +501,36 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
       a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[0][ks], a0, 0, 0, 0);
       a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[1][ks], a1, 0, 0, 0);
     }
-    const int n0 = (t_begin + jt) * CS_BN;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int cc = wave * 32 + q * 8 + (lane >> 5) * 4;
-      const float b0 = bf16_bits_to_float(bv[q].x & 0xffffu), b1 = bf16_bits_to_float(bv[q].x >> 16);
-      const float b2 = bf16_bits_to_float(bv[q].y & 0xffffu), b3 = bf16_bits_to_float(bv[q].y >> 16);
-      uint2 w;
-      w.x = pack_bf16x2(a0[q * 4 + 0] * scale + b0, a0[q * 4 + 1] * scale + b1);
-      w.y = pack_bf16x2(a0[q * 4 + 2] * scale + b2, a0[q * 4 + 3] * scale + b3);
-      *reinterpret_cast<uint2*>(ostage + (lane & 31) * L::OUT_LD + cc * 2) = w;
-      w.x = pack_bf16x2(a1[q * 4 + 0] * scale + b0, a1[q * 4 + 1] * scale + b1);
-      w.y = pack_bf16x2(a1[q * 4 + 2] * scale + b2, a1[q * 4 + 3] * scale + b3);
-      *reinterpret_cast<uint2*>(ostage + (32 + (lane & 31)) * L::OUT_LD + cc * 2) = w;
-    }
-    __syncthreads();
-    constexpr int PPR = CS_BN / 8;  // 16-byte pieces per output row
+    // Result rows leave straight from registers.  A lane holds, per 8-column group q, the
+    // four columns 8 q + 4 (l / 32) .. +3 of its row; exchanging the upper half-wave's part
+    // of an even group with the lower half-wave's part of the odd group next to it
+    // (v_permlane32_swap) leaves every lane with eight consecutive columns -- 16 bytes --
+    // so no trip through LDS, and no barrier, is needed to form whole pieces.
+    const int n0 = (t_begin + jt) * CS_BN + wave * 32;
     const int n_lim = jt < my_tiles ? p.N : 0;
+    auto rows_out = [&](const f32x16& acc, int row0) {
+      const int gm = m0 + row0 + (lane & 31);
 #pragma unroll
-    for (int s = 0; s < (CH_BM * PPR) / 256; ++s) {
-      const int idx = s * 256 + tid;
-      const int r = idx / PPR, pc = idx % PPR;
-      const int gm = m0 + r, gn = n0 + pc * 8;
-      if (gm < p.M && gn < n_lim) {
-        const uint2 lo = *reinterpret_cast<const uint2*>(ostage + r * L::OUT_LD + pc * 16);
-        const uint2 hi = *reinterpret_cast<const uint2*>(ostage + r * L::OUT_LD + pc * 16 + 8);
-        *reinterpret_cast<uint4*>(C + (int64_t)gm * p.ldc + gn) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      for (int pr = 0; pr < 2; ++pr) {
+        uint2 w[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int q = 2 * pr + h;
+          const float b0 = bf16_bits_to_float(bv[q].x & 0xffffu), b1 = bf16_bits_to_float(bv[q].x >> 16);
+          const float b2 = bf16_bits_to_float(bv[q].y & 0xffffu), b3 = bf16_bits_to_float(bv[q].y >> 16);
+          w[h].x = pack_bf16x2(acc[q * 4 + 0] * scale + b0, acc[q * 4 + 1] * scale + b1);
+          w[h].y = pack_bf16x2(acc[q * 4 + 2] * scale + b2, acc[q * 4 + 3] * scale + b3);
+        }
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(w[0].x, w[1].x, false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(w[0].y, w[1].y, false, false);
+        const int gn = n0 + 16 * pr + 8 * (lane >> 5);
+        if (gm < p.M && gn < n_lim)
+          *reinterpret_cast<uint4*>(C + (int64_t)gm * p.ldc + gn) = make_uint4(s0.x, s1.x, s0.y, s1.y);
       }
-    }
+    };
+    rows_out(a0, 0);
+    rows_out(a1, 32);
   };
 
   for (int jt = 0; jt < my_tiles; jt += 2) {
