@@ -32,10 +32,6 @@ __device__ __forceinline__ void sched_phase() {
   }
 }
 
-template <typename OutT> struct OutTraits;
-template <> struct OutTraits<bf16> { static constexpr int PIECE = 8; };    // 4 bf16
-template <> struct OutTraits<float> { static constexpr int PIECE = 16; };  // 4 fp32
-
 // One tile configuration of the GEMM: its work-group size, its LDS footprint and its body
 // (the work of one work-group, given the group's index in the launch and LDS of at
 // least LDS_BYTES).  The body is a device function so that one launch can carry the
@@ -48,10 +44,7 @@ struct GemmTile {
   typedef OpTile<BN, B_KC, BK, NTH> TB;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   static constexpr int STAGE = TA::ELEMS + TB::ELEMS;
-  static constexpr int PIECE = OutTraits<OutT>::PIECE;
-  static constexpr int EP_LD = WN * (int)sizeof(OutT) + PIECE;  // bytes per staged output row
-  static constexpr int EP_BYTES = WAVES_M * WAVES_N * 32 * EP_LD;
-  static constexpr int LDS_BYTES = (2 * STAGE * 2 > EP_BYTES) ? 2 * STAGE * 2 : EP_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE * 2;
   static __device__ __forceinline__ void run(const GemmArgs& p, int block, unsigned char* smem);
 };
 
@@ -230,63 +223,61 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
     }
   }
 
-  // ---- epilogue: accumulators -> per-wave LDS staging -> contiguous row stores ----
+  // ---- epilogue: accumulators -> global, straight from registers ----
   // Lane l owns output row l % 32 of each 32-row block and, for q = 0..3, the four
-  // columns 8 q + 4 (l / 32) .. +3 of each 32-column block.
-  unsigned char* const stage = smem + wave * (32 * EP_LD);
+  // columns 8 q + 4 (l / 32) .. +3 of each 32-column block: 16 bytes of fp32 as they are;
+  // for bf16 the two half-waves exchange the halves of neighbouring column groups
+  // (v_permlane32_swap), after which every lane holds eight consecutive columns.  Either
+  // way a store instruction writes 32-byte row segments, which the L2 merges into lines;
+  // going through LDS to form longer segments cost two barriers per 32-row block.
   OutT* __restrict__ C = static_cast<OutT*>(p.C) +
                          (sizeof(OutT) == 4 ? (int64_t)split * p.M * p.ldc : (int64_t)0);
   const float scale = p.scale;
   const int wn0 = n0 + wn * WN;  // first global column of this wave
   const int n_store = p.n_store > 0 ? p.n_store : p.N;
-  constexpr int PPR = WN * (int)sizeof(OutT) / PIECE;  // pieces per staged row
 
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    const int gm = m0 + wm * WM + i * 32 + (lane & 31);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
+      if constexpr (sizeof(OutT) == 4) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = j * 32 + q * 8 + (lane >> 5) * 4;  // column inside the wave tile
-        float v[4];
+        for (int q = 0; q < 4; ++q) {
+          const int gn = wn0 + j * 32 + q * 8 + (lane >> 5) * 4;
+          if (gm < p.M && gn < n_store)
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)gm * p.ldc + gn) =
+                make_float4(acc[i][j][q * 4 + 0] * scale, acc[i][j][q * 4 + 1] * scale,
+                            acc[i][j][q * 4 + 2] * scale, acc[i][j][q * 4 + 3] * scale);
+        }
+      } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e] * scale;
-        if (sizeof(OutT) == 2) {
-          if constexpr (HAS_BIAS) {
+        for (int pr = 0; pr < 2; ++pr) {
+          uint2 w[2];
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int q = 2 * pr + h;
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e] * scale;
             const uint2 bb = bias_r[j][q];
             v[0] += bf16_bits_to_float(bb.x & 0xffffu);
             v[1] += bf16_bits_to_float(bb.x >> 16);
             v[2] += bf16_bits_to_float(bb.y & 0xffffu);
             v[3] += bf16_bits_to_float(bb.y >> 16);
+            w[h].x = pack_bf16x2(v[0], v[1]);
+            w[h].y = pack_bf16x2(v[2], v[3]);
           }
-          uint2 w;
-          w.x = pack_bf16x2(v[0], v[1]);
-          w.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(stage + (lane & 31) * EP_LD + c * 2) = w;
-        } else {
-          *reinterpret_cast<float4*>(stage + (lane & 31) * EP_LD + c * 4) =
-              make_float4(v[0], v[1], v[2], v[3]);
+          typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+          const u32x2 s0 = __builtin_amdgcn_permlane32_swap(w[0].x, w[1].x, false, false);
+          const u32x2 s1 = __builtin_amdgcn_permlane32_swap(w[0].y, w[1].y, false, false);
+          const int gn = wn0 + j * 32 + 16 * pr + 8 * (lane >> 5);
+          if (gm < p.M && gn < n_store)
+            *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(C) + (int64_t)gm * p.ldc + gn) =
+                make_uint4(s0.x, s1.x, s0.y, s1.y);
         }
       }
     }
-    __syncthreads();
-    const int row_base = m0 + wm * WM + i * 32;
-#pragma unroll
-    for (int it = 0; it < (32 * PPR) / 64; ++it) {
-      const int idx = it * 64 + lane;
-      const int r = idx / PPR, pc = idx % PPR;
-      const int gm = row_base + r, gn = wn0 + pc * 4;
-      if (gm < p.M && gn < n_store) {
-        if (sizeof(OutT) == 2) {
-          const uint2 w = *reinterpret_cast<const uint2*>(stage + r * EP_LD + pc * PIECE);
-          *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(C) + (int64_t)gm * p.ldc + gn) = w;
-        } else {
-          const float4 w = *reinterpret_cast<const float4*>(stage + r * EP_LD + pc * PIECE);
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(C) + (int64_t)gm * p.ldc + gn) = w;
-        }
-      }
-    }
-    __syncthreads();
   }
 
   if (COLSUM) {
