@@ -50,8 +50,8 @@ sk_status check_shape(int64_t tokens, int64_t in, int64_t out, int32_t l, int32_
 }
 
 // Tile choice for the general GEMM (measured on MI355X).  The 256 x 256 tile with eight
-// waves has the best steady state but a long prologue and epilogue, so it only pays
-// with a long contraction; 128 x 128 runs two work-groups per CU, which overlaps one
+// waves has the best steady state (fewest LDS instructions per MFMA) but a long prologue,
+// so it pays from a contraction of 512 on when its tiles fill the chip; 128 x 128 runs two work-groups per CU, which overlaps one
 // tile's stores with the other's MFMAs.  Otherwise: the largest tile that still gives
 // every CU a work-group without being mostly padding, the smallest when the problem
 // cannot fill the chip.
@@ -67,7 +67,7 @@ int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
     int bm, bn;
     tile_dims(t, bm, bn);
     if (bm > m_cap || bn > n_cap) continue;
-    if (t == TILE_256x256_W8 && K / splits < 2048) continue;
+    if (t == TILE_256x256_W8 && K / splits < 512) continue;
     const int64_t wgs = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * splits;
     if (wgs >= NUM_CUS) return t;
   }
