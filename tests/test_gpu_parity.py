@@ -220,6 +220,32 @@ def test_single_call_backward(sk, w):
     assert torch.equal(nob.dU.view(torch.int32), sep.dU.view(torch.int32))
 
 
+def _random_shapes(n, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        l = int(r.integers(1, 5))
+        k = int(r.choice([16, 32, 48, 64, 96]))
+        out.append(W.Workload(f"rnd{i}", int(r.integers(1, 900)), 16 * int(r.integers(1, 40)),
+                              16 * int(r.integers(1, 40)), l, k, "f32" if i % 6 == 5 else "bf16", seed=100 + i))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_shapes(24, 2024), ids=lambda w: f"{w.name}_T{w.tokens}_{w.d_in}x{w.d_out}_l{w.l}k{w.k}_{w.dtype}")
+def test_random_shapes(sk, w):
+    """Seeded random shapes (ragged token counts, every multiple of 16 for the feature sizes,
+    sketch widths on both sides of every plan boundary), automatic plan, three calls and
+    the single-call backward."""
+    check_all(sk, w, 0)
+    t = W.generate(w)
+    dev = DeviceLayer(t, sk)
+    sk.check(dev.bwd())
+    torch.cuda.synchronize()
+    want = oracle_all(t)
+    for n, got in (("dX", dev.dX), ("dU", dev.dU), ("db", dev.db)):
+        assert rel_err(to_f64(got), want[n]) <= TOL[w.dtype], n
+
+
 def test_forced_big_tiles(sk, monkeypatch):
     """The large-shape code paths (big tiles, the bias gradient from its own kernel)
     on a shape small enough for a full oracle pass."""
