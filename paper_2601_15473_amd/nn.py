@@ -172,3 +172,110 @@ class SKLinear(torch.nn.Module):
     def extra_repr(self) -> str:
         return (f"in_features={self.in_features}, out_features={self.out_features}, "
                 f"num_terms={self.num_terms}, low_rank={self.low_rank}, bias={self.bias is not None}")
+
+
+class SKLinearTwoSidedFunction(torch.autograd.Function):
+    """The two-sided reading of the layer (2 l terms: l sketch the input side, l the output
+    side; see include/sk.h, sk_linear_bwd_weight_first):
+
+        y = 1/(2l) * sum_i [ (x . S1_i) . U1_i + (x . U2_i) . S2_i^T ] + b
+
+    Arguments: S1_cat [in, l*k] and S2T_cat [l*k, out] fixed, U1_cat [l*k, out] and U2_cat
+    [in, l*k] learned.  The layer is the one-sided chain on [S1 | U2] and [U1 ; S2^T] with 2 l
+    terms; the two concatenations are copies made here, everything else runs in libsk."""
+
+    @staticmethod
+    def forward(ctx, x, S1_cat, U1_cat, U2_cat, S2T_cat, bias, l, k):
+        dtype = S1_cat.dtype
+        if dtype not in _DTYPES:
+            raise TypeError(f"SKLinear: dtype {dtype} is not supported (float32 or bfloat16)")
+        for t, n in ((x, "x"), (S1_cat, "S1_cat"), (U1_cat, "U1_cat"), (U2_cat, "U2_cat"), (S2T_cat, "S2T_cat")):
+            _check(t, n, dtype)
+        d_in, half = S1_cat.shape
+        d_out = U1_cat.shape[1]
+        if half != l * k or U1_cat.shape[0] != half or U2_cat.shape != (d_in, half) or \
+                S2T_cat.shape != (half, d_out) or x.shape[-1] != d_in:
+            raise ValueError("SKLinear (two-sided): shapes do not match")
+        A_cat = torch.cat([S1_cat, U2_cat], dim=1).contiguous()
+        B_cat = torch.cat([U1_cat, S2T_cat], dim=0).contiguous()
+        x2 = x.reshape(-1, d_in).contiguous()
+        bias_c = bias.contiguous() if bias is not None else None
+        tokens = x2.shape[0]
+        y = torch.empty((tokens, d_out), dtype=dtype, device=x.device)
+        args = (tokens, d_in, d_out, 2 * l, k, _DTYPES[dtype])
+        with torch.cuda.device(x.device):
+            stream = torch.cuda.current_stream().cuda_stream
+            need = sk.sk_linear_workspace_bytes(sk.SK_OP_FWD, *args)
+            if need == 2 ** 64 - 1:
+                raise sk.SkError(sk.SK_ERR_UNSUPPORTED)
+            ws = _workspace(x.device, stream, need)
+            sk.check(sk.sk_linear_fwd(x2, A_cat, B_cat, bias_c, y, *args, ws, ws.numel(), stream))
+        ctx.save_for_backward(x2, A_cat, B_cat)
+        ctx.args, ctx.x_shape, ctx.has_bias, ctx.half = args, x.shape, bias is not None, half
+        return y.reshape(*x.shape[:-1], d_out)
+
+    @staticmethod
+    def backward(ctx, dY):
+        x2, A_cat, B_cat = ctx.saved_tensors
+        tokens, d_in, d_out, l2, k, dt = ctx.args
+        dtype, half = A_cat.dtype, ctx.half
+        dY2 = dY.reshape(-1, d_out).to(dtype).contiguous()
+        dev = dY.device
+        with torch.cuda.device(dev):
+            stream = torch.cuda.current_stream().cuda_stream
+            need = max(sk.sk_linear_workspace_bytes(op, *ctx.args)
+                       for op in (sk.SK_OP_BWD, sk.SK_OP_BWD_WEIGHT_FIRST))
+            ws = _workspace(dev, stream, need)
+            dX = torch.empty((tokens, d_in), dtype=dtype, device=dev)
+            dB = torch.empty((2 * half, d_out), dtype=torch.float32, device=dev)
+            db = torch.empty((d_out,), dtype=torch.float32, device=dev) if ctx.has_bias else None
+            dA = torch.empty((d_in, half), dtype=torch.float32, device=dev)
+            sk.check(sk.sk_linear_bwd(x2, dY2, A_cat, B_cat, dX, dB, db, *ctx.args, ws, ws.numel(), stream))
+            sk.check(sk.sk_linear_bwd_weight_first(x2, B_cat, dY2, dA, tokens, d_in, d_out, l2, k,
+                                                   half, half, dt, ws, ws.numel(), stream))
+        # the rows of dB below `half` belong to S2^T: gradients of fixed numbers, dropped
+        return (dX.reshape(ctx.x_shape), None, dB[:half].to(dtype), dA.to(dtype), None,
+                db.to(dtype) if db is not None else None, None, None)
+
+
+class SKLinearTwoSided(torch.nn.Module):
+    """``SKLinear`` in its two-sided reading: ``num_terms`` terms per side.  Initialised from
+    a dense layer's weights the way ``SKLinear`` is: U1_i = S1_i^T W^T, U2_i = W^T S2_i."""
+
+    def __init__(self, in_features: int, out_features: int, num_terms: int = 1, low_rank: int = 16,
+                 bias: bool = True, dtype: torch.dtype = torch.bfloat16, device="cuda", seed: int | None = None):
+        super().__init__()
+        if dtype not in _DTYPES:
+            raise TypeError(f"SKLinear: dtype {dtype} is not supported (float32 or bfloat16)")
+        device = torch.device(device)
+        if device.type != "cuda":
+            raise RuntimeError("SKLinear: libsk runs on the GPU only (there is no CPU implementation)")
+        self.in_features, self.out_features = in_features, out_features
+        self.num_terms, self.low_rank = num_terms, low_rank
+        half = num_terms * low_rank
+        g = torch.Generator(device="cpu")
+        if seed is not None:
+            g.manual_seed(seed)
+        else:
+            g.seed()
+        S1 = (torch.randn(in_features, half, generator=g) / math.sqrt(low_rank)).to(dtype).to(device)
+        S2T = (torch.randn(half, out_features, generator=g) / math.sqrt(low_rank)).to(dtype).to(device)
+        bound = 1.0 / math.sqrt(in_features)
+        W = ((torch.rand(out_features, in_features, generator=g) * 2 - 1) * bound).to(device)
+        self.register_buffer("S1_cat", S1)
+        self.register_buffer("S2T_cat", S2T)
+        self.U1_cat = torch.nn.Parameter((S1.float().t() @ W.t()).to(dtype))       # [l*k, out]
+        self.U2_cat = torch.nn.Parameter((W.t() @ S2T.float().t()).to(dtype))      # [in, l*k]
+        if bias:
+            b = (torch.rand(out_features, generator=g) * 2 - 1) * bound
+            self.bias = torch.nn.Parameter(b.to(dtype).to(device))
+        else:
+            self.register_parameter("bias", None)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        return SKLinearTwoSidedFunction.apply(x, self.S1_cat, self.U1_cat, self.U2_cat, self.S2T_cat,
+                                              self.bias, self.num_terms, self.low_rank)
+
+    def extra_repr(self) -> str:
+        return (f"in_features={self.in_features}, out_features={self.out_features}, "
+                f"num_terms={self.num_terms} per side, low_rank={self.low_rank}, bias={self.bias is not None}")

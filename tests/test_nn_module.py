@@ -90,3 +90,38 @@ def test_no_grad_inputs_skip_their_kernels():
     m(x).sum().backward()
     assert m.U_cat.grad is not None and m.U_cat.grad.dtype == torch.bfloat16
     assert x.grad is None and m.bias is None
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,tol", [(torch.bfloat16, 2e-2), (torch.float32, 1e-4)], ids=["bf16", "f32"])
+def test_two_sided_module_matches_its_oracle(dtype, tol):
+    from oracle import sklinear_two_sided as O2
+    from paper_2601_15473_amd import nn as sknn
+    from skgpu import rel_err, to_f64
+    l, k, d_in, d_out, T = 2, 16, 96, 80, 150
+    print(f"case nn two-sided {dtype} T={T} {d_in}->{d_out} l={l}+{l} k={k}", flush=True)
+    m = sknn.SKLinearTwoSided(d_in, d_out, l, k, bias=True, dtype=dtype, seed=21)
+    g = torch.Generator().manual_seed(22)
+    x = torch.randn(T, d_in, generator=g).to(dtype).cuda().requires_grad_(True)
+    dY = torch.randn(T, d_out, generator=g).to(dtype).cuda()
+    y = m(x)
+    y.backward(dY)
+    S1c, U1c, U2c, S2Tc = (to_f64(t) for t in (m.S1_cat, m.U1_cat, m.U2_cat, m.S2T_cat))
+    S1 = np.stack([S1c[:, i * k:(i + 1) * k] for i in range(l)])             # [l, in, k]
+    U2 = np.stack([U2c[:, i * k:(i + 1) * k] for i in range(l)])
+    U1 = np.stack([U1c[i * k:(i + 1) * k] for i in range(l)])                # [l, k, out]
+    S2 = np.stack([S2Tc[i * k:(i + 1) * k].T for i in range(l)])             # [l, out, k]
+    x64, dY64 = to_f64(x), to_f64(dY)
+    want = dict(
+        y=O2.forward(x64, S1, U1, U2, S2, to_f64(m.bias)),
+        dX=O2.grad_input(dY64, S1, U1, U2, S2),
+        dU1=O2.grad_second_stage(x64, S1, dY64).reshape(l * k, d_out),
+        dU2=np.transpose(O2.grad_first_stage(x64, S2, dY64), (1, 0, 2)).reshape(d_in, l * k),
+        db=O2.grad_bias(dY64),
+    )
+    got = dict(y=to_f64(y), dX=to_f64(x.grad), dU1=to_f64(m.U1_cat.grad), dU2=to_f64(m.U2_cat.grad),
+               db=to_f64(m.bias.grad))
+    for n in want:
+        e = rel_err(got[n], want[n])
+        print(f"   {n}: {e:.2e}", flush=True)
+        assert e <= tol, (n, e)
