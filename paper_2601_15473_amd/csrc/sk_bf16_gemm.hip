@@ -14,24 +14,6 @@
 
 namespace sk {
 
-// One scheduling phase: NM MFMAs with ND LDS reads, NV global loads and NW LDS stores
-// spread evenly between them, then a fence for the scheduler.
-template <int NM, int ND, int NV, int NW, int I = 0>
-__device__ __forceinline__ void sched_phase() {
-  if constexpr (I < NM) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    constexpr int d = (I + 1) * ND / NM - I * ND / NM;
-    constexpr int v = (I + 1) * NV / NM - I * NV / NM;
-    constexpr int w = (I + 1) * NW / NM - I * NW / NM;
-    if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x100, d, 0);
-    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
-    if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
-    sched_phase<NM, ND, NV, NW, I + 1>();
-  } else {
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
 // One tile configuration of the GEMM: its work-group size, its LDS footprint and its body
 // (the work of one work-group, given the group's index in the launch and LDS of at
 // least LDS_BYTES).  The body is a device function so that one launch can carry the

@@ -66,6 +66,37 @@ __device__ __forceinline__ int kc_piece(int row, int pc) {
   return pc ^ ((row / ROWS_PER_BANKROW) & (PPR - 1));
 }
 
+// Compile-time loop: f(IntC<I>{}) for I = BEGIN .. END - 1.
+template <int V>
+struct IntC {
+  static constexpr int value = V;
+};
+template <int BEGIN, int END, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(IntC<BEGIN>{});
+    static_for<BEGIN + 1, END>(f);
+  }
+}
+
+// One scheduling phase: NM MFMAs with ND LDS reads, NV global loads and NW LDS stores
+// spread evenly between them, then a fence for the scheduler.
+template <int NM, int ND, int NV, int NW, int I = 0>
+__device__ __forceinline__ void sched_phase() {
+  if constexpr (I < NM) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    constexpr int d = (I + 1) * ND / NM - I * ND / NM;
+    constexpr int v = (I + 1) * NV / NM - I * NV / NM;
+    constexpr int w = (I + 1) * NW / NM - I * NW / NM;
+    if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x100, d, 0);
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+    if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+    sched_phase<NM, ND, NV, NW, I + 1>();
+  } else {
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int EXT, bool KC, int KX = BK, int NTH = 256>
 struct OpTile {
   static constexpr int LD = KC ? KX : EXT + 32;
@@ -78,6 +109,9 @@ struct OpTile {
   // row/col ext0 and k0; k is clipped at k_end and ext at ext_total; everything
   // outside reads as zero.  Extents along a contiguous dimension are multiples of
   // 8, so a 16-byte piece is wholly inside or wholly outside.
+  // (P0, P1 select a run of the thread's pieces, for callers that spread a tile's loads
+  // over several scheduling phases.)
+  template <int P0 = 0, int P1 = PIECES>
   static __device__ __forceinline__ void load(uint4 (&r)[PIECES], const bf16* __restrict__ g,
                                               int64_t ld, int ext0, int ext_total, int k0,
                                               int k_end, int k_total, int tid) {
@@ -86,7 +120,7 @@ struct OpTile {
     const GWindow w = make_window(g, origin, rows * ld, 2);
     const unsigned ldb = (unsigned)ld * 2u;
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) {
+    for (int p = P0; p < P1; ++p) {
       const int piece = p * NTH + tid;
       constexpr int PPR = KC ? KX / 8 : EXT / 8;
       const int row = piece / PPR, col = (piece % PPR) * 8;
@@ -97,10 +131,11 @@ struct OpTile {
     }
   }
 
-  // Registers -> LDS tile.
+  // Registers -> LDS tile (pieces P0 .. P1 - 1 of the thread).
+  template <int P0 = 0, int P1 = PIECES>
   static __device__ __forceinline__ void store(bf16* tile, const uint4 (&r)[PIECES], int tid) {
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) {
+    for (int p = P0; p < P1; ++p) {
       const int piece = p * NTH + tid;
       constexpr int PPR = KC ? KX / 8 : EXT / 8;
       const int row = piece / PPR;

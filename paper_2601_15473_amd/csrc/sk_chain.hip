@@ -278,6 +278,22 @@ struct SmallLds {
   static constexpr int BYTES = HEAD_BYTES + (S1_BYTES > S2_BYTES ? S1_BYTES : S2_BYTES);
 };
 
+// Scheduling of one stage-2 tile of the narrow kernel: per k step the fragment reads of
+// the next step (ND LDS reads), two MFMAs, one or two of the KS + 4 global loads and one
+// of the KS LDS stores.
+template <int KS, int ND, int I = 0>
+__device__ __forceinline__ void sched_stage2() {
+  if constexpr (I < KS) {
+    if constexpr (I + 1 < KS) __builtin_amdgcn_sched_group_barrier(0x100, ND, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, I < 4 ? 2 : 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    sched_stage2<KS, ND, I + 1>();
+  } else {
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
 __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   typedef SmallLds<RT, B2_KC, FUSED, B1_KC> L;
@@ -361,47 +377,70 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
     uint4 xa0[TA::PIECES], xb0[TB1::PIECES], xa1[TA::PIECES], xb1[TB1::PIECES];
     const int nk = (p.K1 + BK - 1) / BK;
     // chunks past K1 load as zeros, so the loop needs no branch around its loads
-    auto load0 = [&](int kc) {
-      TA::load(xa0, A, p.lda, m0, p.M, kc * BK, p.K1, p.K1, tid);
-      TB1::load(xb0, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
+    auto load_a = [&](uint4 (&r)[TA::PIECES], int kc) {
+      TA::load(r, A, p.lda, m0, p.M, kc * BK, p.K1, p.K1, tid);
     };
-    auto load1 = [&](int kc) {
-      TA::load(xa1, A, p.lda, m0, p.M, kc * BK, p.K1, p.K1, tid);
-      TB1::load(xb1, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
+    constexpr int HB = TB1::PIECES / 2;
+    auto load_b_lo = [&](uint4 (&r)[TB1::PIECES], int kc) {
+      TB1::template load<0, HB>(r, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
     };
-    auto compute = [&](const bf16* As) {
-      const bf16* Bs = As + TA::ELEMS;
+    auto load_b_hi = [&](uint4 (&r)[TB1::PIECES], int kc) {
+      TB1::template load<HB, TB1::PIECES>(r, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
+    };
+    bf16x8 fa0, fa1, fb0[TN1], fb1[TN1];
+    auto rd = [&](const bf16* As, int ks, bf16x8& fa, bf16x8 (&fb)[TN1]) {
+      fa = read_frag<true, TA::LD>(As, wm * 32, ks, lane);
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        const bf16x8 fa = read_frag<true, TA::LD>(As, wm * 32, ks, lane);
-#pragma unroll
-        for (int j = 0; j < TN1; ++j) {
-          const bf16x8 fb = read_frag<B1_KC, TB1::LD>(Bs, wn * (RT / 2) + j * 32, ks, lane);
-          acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc1[j], 0, 0, 0);
-        }
-      }
+      for (int j = 0; j < TN1; ++j)
+        fb[j] = read_frag<B1_KC, TB1::LD>(As + TA::ELEMS, wn * (RT / 2) + j * 32, ks, lane);
     };
-    load0(0);
-    load1(1);
+    auto mm = [&](const bf16x8& fa, const bf16x8 (&fb)[TN1]) {
+#pragma unroll
+      for (int j = 0; j < TN1; ++j)
+        acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa, acc1[j], 0, 0, 0);
+    };
+    // LDS read instructions of one k step: one for the x fragment, one (k-contiguous B1)
+    // or two (transposing reads) per B1 fragment
+    constexpr int NDS = 1 + TN1 * (B1_KC ? 1 : 2);
+    // One chunk: MFMAs on the chunk in `As`, the loads of the chunk two ahead (into la,
+    // lb) and the LDS stores of the next chunk (from sa, sb, loaded an iteration ago)
+    // spread between them -- issued in one burst the loads hold every wave at the
+    // memory pipe's queue while LDS and MFMA sit idle.
+    auto iteration = [&](const bf16* As, bf16* An, uint4 (&la)[TA::PIECES], uint4 (&lb)[TB1::PIECES],
+                         uint4 (&sa)[TA::PIECES], uint4 (&sb)[TB1::PIECES], int kc_load) {
+      rd(As, 0, fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      rd(As, 1, fa1, fb1);
+      load_a(la, kc_load);
+      mm(fa0, fb0);
+      sched_phase<TN1, NDS, TA::PIECES, 0>();
+      rd(As, 2, fa0, fb0);
+      load_b_lo(lb, kc_load);
+      mm(fa1, fb1);
+      sched_phase<TN1, NDS, HB, 0>();
+      rd(As, 3, fa1, fb1);
+      load_b_hi(lb, kc_load);
+      mm(fa0, fb0);
+      TA::store(An, sa, tid);
+      sched_phase<TN1, NDS, TB1::PIECES - HB, TA::PIECES>();
+      mm(fa1, fb1);
+      TB1::store(An + TA::ELEMS, sb, tid);
+      sched_phase<TN1, 0, 0, TB1::PIECES>();
+      __syncthreads();
+    };
+    load_a(xa0, 0);
+    load_b_lo(xb0, 0);
+    load_b_hi(xb0, 0);
+    load_a(xa1, 1);
+    load_b_lo(xb1, 1);
+    load_b_hi(xb1, 1);
     TA::store(s1, xa0, tid);
     TB1::store(s1 + TA::ELEMS, xb0, tid);
     __syncthreads();
     for (int kc = 0; kc < nk; kc += 2) {
       // chunk kc sits in buffer 0; set 1 holds chunk kc + 1 (in flight or landed)
-      load0(kc + 2);
-      __builtin_amdgcn_sched_barrier(0);  // keep the new loads ahead of the wait for the old ones
-      compute(s1);
-      __builtin_amdgcn_sched_barrier(0);
-      TA::store(s1 + STAGE, xa1, tid);
-      TB1::store(s1 + STAGE + TA::ELEMS, xb1, tid);
-      __syncthreads();
-      load1(kc + 3);
-      __builtin_amdgcn_sched_barrier(0);
-      compute(s1 + STAGE);  // an all-zero chunk when nk is odd
-      __builtin_amdgcn_sched_barrier(0);
-      TA::store(s1, xa0, tid);
-      TB1::store(s1 + TA::ELEMS, xb0, tid);
-      __syncthreads();
+      iteration(s1, s1 + STAGE, xa0, xb0, xa1, xb1, kc + 2);
+      iteration(s1 + STAGE, s1, xa1, xb1, xa0, xb0, kc + 3);  // an all-zero chunk when nk is odd
     }
 #pragma unroll
     for (int j = 0; j < TN1; ++j)
@@ -490,17 +529,32 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   bf16* __restrict__ C = static_cast<bf16*>(p.C);
   const float scale = p.scale;
 
-  // one [64 x 128] output tile: wave w owns columns 32 w .. 32 w + 31 of it
-  auto tile = [&](int jt, const bf16* Bs, const uint2 (&bv)[4]) {
+  // One [64 x 128] output tile (wave w owns columns 32 w .. 32 w + 31 of it) from the B2
+  // tile in `Bs`.  Between its MFMAs go the loads of the tile two ahead (into rl), the
+  // next tile's bias (into bvn) and the LDS stores of the next tile (from rs, loaded one
+  // step ago, into Bn): issued in one burst, the loads hold every wave at the memory
+  // pipe's queue while LDS and MFMA sit idle.
+  auto step = [&](int jt, const bf16* Bs, bf16* Bn, const uint2 (&bv)[4], uint2 (&bvn)[4],
+                  uint4 (&rl)[TB2::PIECES], uint4 (&rs)[TB2::PIECES]) {
     f32x16 a0, a1;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8 fb = read_frag<B2_KC, TB2::LD>(Bs, wave * 32, ks, lane);
+    bf16x8 fb = read_frag<B2_KC, TB2::LD>(Bs, wave * 32, 0, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    load_bias(bvn, jt + 1);
+    load_b2(rl, jt + 2);
+    // (an LDS store may not pass an LDS read in the compiler's eyes, so each k step's
+    // store sits where the schedule wants it: after the reads of the step that follows)
+    static_for<0, KS>([&](auto ksc) {
+      constexpr int ks = decltype(ksc)::value;
+      bf16x8 fbn = fb;
+      if (ks + 1 < KS) fbn = read_frag<B2_KC, TB2::LD>(Bs, wave * 32, ks + 1, lane);
       a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[0][ks], a0, 0, 0, 0);
       a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[1][ks], a1, 0, 0, 0);
-    }
+      TB2::template store<ks, ks + 1>(Bn, rs, tid);
+      fb = fbn;
+    });
+    sched_stage2<KS, B2_KC ? 1 : 2>();
     // Result rows leave straight from registers.  A lane holds, per 8-column group q, the
     // four columns 8 q + 4 (l / 32) .. +3 of its row; exchanging the upper half-wave's part
     // of an even group with the lower half-wave's part of the odd group next to it
@@ -531,24 +585,14 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
     };
     rows_out(a0, 0);
     rows_out(a1, 32);
+    __syncthreads();
   };
 
   for (int jt = 0; jt < my_tiles; jt += 2) {
     // tile jt sits in buffer 0; set 1 holds tile jt + 1
-    load_bias(bv1, jt + 1);
-    load_b2(rb0, jt + 2);
-    __builtin_amdgcn_sched_barrier(0);  // keep the new loads ahead of the wait for the old ones
-    tile(jt, Bbuf, bv0);
-    __builtin_amdgcn_sched_barrier(0);
-    TB2::store(Bbuf + TB2::ELEMS, rb1, tid);
-    __syncthreads();
-    load_bias(bv0, jt + 2);
-    load_b2(rb1, jt + 3);
-    __builtin_amdgcn_sched_barrier(0);
-    tile(jt + 1, Bbuf + TB2::ELEMS, bv1);  // computes on zeros and stores nothing past the run
-    __builtin_amdgcn_sched_barrier(0);
-    TB2::store(Bbuf, rb0, tid);
-    __syncthreads();
+    step(jt, Bbuf, Bbuf + TB2::ELEMS, bv0, bv1, rb0, rb1);
+    // (computes on zeros and stores nothing past the run)
+    step(jt + 1, Bbuf + TB2::ELEMS, Bbuf, bv1, bv0, rb1, rb0);
   }
 }
 
