@@ -178,17 +178,19 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
     __syncthreads();
     auto iteration = [&](const bf16* As, bf16* An, uint4 (&la)[TA::PIECES], uint4 (&lb)[TB::PIECES],
                          uint4 (&sa)[TA::PIECES], uint4 (&sb)[TB::PIECES], int k0) {
-      // loads into (la, lb) for chunk k0; stores from (sa, sb), loaded an iteration ago
+      // loads into (la, lb) for chunk k0, A's during k step 0 and B's during k step 1 (in
+      // one burst they hold the waves at the memory pipe's queue; measured 1 % on the
+      // [8192 x 1024..4096] shapes); stores from (sa, sb), loaded an iteration ago
       read(As, 0, fa0, fb0);
       __builtin_amdgcn_sched_barrier(0);
       read(As, 1, fa1, fb1);
       TA::load(la, A, p.lda, m0, p.M, k0, k_end, p.K, tid);
-      TB::load(lb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
       mma(fa0, fb0);
-      sched_phase<NMMA, NDSR, NVM, 0>();
+      sched_phase<NMMA, NDSR, TA::PIECES, 0>();
       read(As, 2, fa0, fb0);
+      TB::load(lb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
       mma(fa1, fb1);
-      sched_phase<NMMA, NDSR, 0, 0>();
+      sched_phase<NMMA, NDSR, TB::PIECES, 0>();
       read(As, 3, fa1, fb1);
       mma(fa0, fb0);
       TA::store(An, sa, tid);
