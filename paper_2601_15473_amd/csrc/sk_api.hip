@@ -240,15 +240,30 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
   return q;
 }
 
-// Number of N slices of the expand/fused kernel: one work-group per CU.
-int chain_slices(int64_t T, int64_t N, int R) {
-  const int64_t tiles_m = (T + 63) / 64;
+// Shape of the expand/fused launch: rows of a token tile and the number of N slices (one
+// work-group per CU).
+struct ChainShape {
+  int bm, slices;
+};
+ChainShape chain_shape(int64_t T, int64_t N, int R) {
+  ChainShape c;
+  // 128-row token tiles halve the B2 traffic and the LDS reads per MFMA of stage 2; they
+  // pay once their tiles alone fill the chip (measured on [T x 768 -> 3072], R = 128:
+  // forward -14..16 % from 65536 tokens on, +17 % at 4096 tokens, where they double the
+  // number of work-groups that repeat stage 1)
+  c.bm = (R <= 128 && T >= 128 * (int64_t)NUM_CUS) ? 128 : 64;
+  if (const char* e = getenv("SK_TUNE_BM")) {  // tuning experiments and tests only
+    const int v = atoi(e);
+    if (v == 64 || (v == 128 && R <= 128)) c.bm = v;
+  }
+  const int64_t tiles_m = (T + c.bm - 1) / c.bm;
   const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
   int64_t sl = NUM_CUS / tiles_m;
   if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
-  return (int)sl;
+  c.slices = (int)sl;
+  return c;
 }
 
 // Workspace of the first-stage gradient for nc columns: G = dY . U_sub^T [T, nc] in the
@@ -362,7 +377,7 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
     c.A = x; c.B1 = S_cat; c.B2 = U_cat; c.bias = bias; c.C = y;
     c.lda = in; c.ldb1 = s.R; c.ldb2 = out; c.ldc = out;
     c.M = (int)tokens; c.K1 = (int)in; c.R = s.R; c.N = (int)out; c.scale = scale;
-    c.n_slices = chain_slices(tokens, out, s.R);
+    { const ChainShape cs = chain_shape(tokens, out, s.R); c.n_slices = cs.slices; c.bm = cs.bm; }
     if (plan == PLAN_SPLIT_EXPAND) {
       const SketchPlan q = plan_sketch(s, in);
       GemmArgs a = dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr);
@@ -406,7 +421,7 @@ sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_c
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-    c.n_slices = chain_slices(tokens, in, s.R);
+    { const ChainShape cs = chain_shape(tokens, in, s.R); c.n_slices = cs.slices; c.bm = cs.bm; }
     if (plan == PLAN_SPLIT_EXPAND) {
       const SketchPlan q = plan_sketch(s, out);
       GemmArgs a = dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr);
@@ -560,7 +575,7 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-    c.n_slices = chain_slices(tokens, in, s.R);
+    { const ChainShape cs = chain_shape(tokens, in, s.R); c.n_slices = cs.slices; c.bm = cs.bm; }
     c.Z = ws_in; c.z_splits = q.splits; c.z_slab = (int64_t)tokens * s.R;
     // Z^T.dY, then the expansion of dX carrying the sum of the token splits
     e = launch_gemm_bf16(du_kind, w.tile, du, hs);

@@ -265,13 +265,13 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
 // ---------------------------------------------------------------------------
 constexpr int CS_BN = 128;
 
-template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
+template <int MB, int RT, bool B2_KC, bool FUSED, bool B1_KC>
 struct SmallLds {
   typedef OpTile<CS_BN, B2_KC, RT> TB2;
-  typedef OpTile<CH_BM, true> TA;
+  typedef OpTile<MB, true> TA;
   typedef OpTile<RT, B1_KC> TB1;
   static constexpr int Z_LD = RT + 8;
-  static constexpr int Z_BYTES = CH_BM * Z_LD * 2;
+  static constexpr int Z_BYTES = MB * Z_LD * 2;
   static constexpr int HEAD_BYTES = Z_BYTES;
   static constexpr int S2_BYTES = 2 * TB2::ELEMS * 2;
   static constexpr int S1_BYTES = FUSED ? 2 * (TA::ELEMS + TB1::ELEMS) * 2 : 0;
@@ -279,26 +279,32 @@ struct SmallLds {
 };
 
 // Scheduling of one stage-2 tile of the narrow kernel: per k step the fragment reads of
-// the next step (ND LDS reads), two MFMAs, one or two of the KS + 4 global loads and one
-// of the KS LDS stores.
-template <int KS, int ND, int I = 0>
+// the next step (ND LDS reads), the step's NM MFMAs, one or two of the KS + 4 global loads
+// and one of the KS LDS stores.
+template <int KS, int ND, int NM, int I = 0>
 __device__ __forceinline__ void sched_stage2() {
   if constexpr (I < KS) {
     if constexpr (I + 1 < KS) __builtin_amdgcn_sched_group_barrier(0x100, ND, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
     __builtin_amdgcn_sched_group_barrier(0x020, I < 4 ? 2 : 1, 0);
     __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-    sched_stage2<KS, ND, I + 1>();
+    sched_stage2<KS, ND, NM, I + 1>();
   } else {
     __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
+template <int MB, int RT, bool B2_KC, bool FUSED, bool B1_KC>
 __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
-  typedef SmallLds<RT, B2_KC, FUSED, B1_KC> L;
+  static_assert(MB == 64 || MB == 128, "token tiles are 64 or 128 rows");
+  typedef SmallLds<MB, RT, B2_KC, FUSED, B1_KC> L;
   typedef typename L::TB2 TB2;
   constexpr int KS = RT / 16;
+  constexpr int MT = MB / 32;   // 32-row blocks of the token tile (stage 2: all of them in every wave)
+  // stage 1: waves 2 x 2, each MB/2 rows x RT/2 columns of Zt (a 1 x 4 grid, with fewer
+  // LDS reads per MFMA when B1 is read transposed, measured no faster)
+  constexpr int WM1 = MB / 2, WN1 = RT / 2;
+  constexpr int TM1 = WM1 / 32, TN1 = WN1 / 32;
   __shared__ __attribute__((aligned(16))) unsigned char smem[L::BYTES];
   bf16* const Zs = reinterpret_cast<bf16*>(smem);
   unsigned char* const work = smem + L::HEAD_BYTES;
@@ -308,7 +314,7 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   const int wm = wave >> 1, wn = wave & 1;  // stage-1 wave grid
   const int wg = xcd_remap(blockIdx.x, p.tiles_m * p.n_slices);
   const int tile_m = wg / p.n_slices, slice = wg % p.n_slices;
-  const int m0 = tile_m * CH_BM;
+  const int m0 = tile_m * MB;
 
   const int n_tiles = (p.N + CS_BN - 1) / CS_BN;
   const int per_slice = (n_tiles + p.n_slices - 1) / p.n_slices;
@@ -365,15 +371,16 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
     typedef typename L::TA TA;
     typedef typename L::TB1 TB1;
     constexpr int STAGE = TA::ELEMS + TB1::ELEMS;
-    constexpr int TN1 = RT / 64;
     bf16* const s1 = reinterpret_cast<bf16*>(work);
     const bf16* __restrict__ A = static_cast<const bf16*>(p.A);
     const bf16* __restrict__ B1 = static_cast<const bf16*>(p.B1);
-    f32x16 acc1[TN1];
+    f32x16 acc1[TM1][TN1];
 #pragma unroll
-    for (int j = 0; j < TN1; ++j)
+    for (int i = 0; i < TM1; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc1[j][r] = 0.f;
+      for (int j = 0; j < TN1; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc1[i][j][r] = 0.f;
     uint4 xa0[TA::PIECES], xb0[TB1::PIECES], xa1[TA::PIECES], xb1[TB1::PIECES];
     const int nk = (p.K1 + BK - 1) / BK;
     // chunks past K1 load as zeros, so the loop needs no branch around its loads
@@ -387,21 +394,25 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
     auto load_b_hi = [&](uint4 (&r)[TB1::PIECES], int kc) {
       TB1::template load<HB, TB1::PIECES>(r, B1, p.ldb1, 0, p.R, kc * BK, p.K1, p.K1, tid);
     };
-    bf16x8 fa0, fa1, fb0[TN1], fb1[TN1];
-    auto rd = [&](const bf16* As, int ks, bf16x8& fa, bf16x8 (&fb)[TN1]) {
-      fa = read_frag<true, TA::LD>(As, wm * 32, ks, lane);
+    bf16x8 fa0[TM1], fa1[TM1], fb0[TN1], fb1[TN1];
+    auto rd = [&](const bf16* As, int ks, bf16x8 (&fa)[TM1], bf16x8 (&fb)[TN1]) {
+#pragma unroll
+      for (int i = 0; i < TM1; ++i) fa[i] = read_frag<true, TA::LD>(As, wm * WM1 + i * 32, ks, lane);
 #pragma unroll
       for (int j = 0; j < TN1; ++j)
-        fb[j] = read_frag<B1_KC, TB1::LD>(As + TA::ELEMS, wn * (RT / 2) + j * 32, ks, lane);
+        fb[j] = read_frag<B1_KC, TB1::LD>(As + TA::ELEMS, wn * WN1 + j * 32, ks, lane);
     };
-    auto mm = [&](const bf16x8& fa, const bf16x8 (&fb)[TN1]) {
+    auto mm = [&](const bf16x8 (&fa)[TM1], const bf16x8 (&fb)[TN1]) {
 #pragma unroll
-      for (int j = 0; j < TN1; ++j)
-        acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa, acc1[j], 0, 0, 0);
+      for (int i = 0; i < TM1; ++i)
+#pragma unroll
+        for (int j = 0; j < TN1; ++j)
+          acc1[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc1[i][j], 0, 0, 0);
     };
-    // LDS read instructions of one k step: one for the x fragment, one (k-contiguous B1)
-    // or two (transposing reads) per B1 fragment
-    constexpr int NDS = 1 + TN1 * (B1_KC ? 1 : 2);
+    // LDS read instructions of one k step: one per x fragment, one (k-contiguous B1) or
+    // two (transposing reads) per B1 fragment
+    constexpr int NDS = TM1 + TN1 * (B1_KC ? 1 : 2);
+    constexpr int NM1 = TM1 * TN1;
     // One chunk: MFMAs on the chunk in `As`, the loads of the chunk two ahead (into la,
     // lb) and the LDS stores of the next chunk (from sa, sb, loaded an iteration ago)
     // spread between them -- issued in one burst the loads hold every wave at the
@@ -413,19 +424,19 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
       rd(As, 1, fa1, fb1);
       load_a(la, kc_load);
       mm(fa0, fb0);
-      sched_phase<TN1, NDS, TA::PIECES, 0>();
+      sched_phase<NM1, NDS, TA::PIECES, 0>();
       rd(As, 2, fa0, fb0);
       load_b_lo(lb, kc_load);
       mm(fa1, fb1);
-      sched_phase<TN1, NDS, HB, 0>();
+      sched_phase<NM1, NDS, HB, 0>();
       rd(As, 3, fa1, fb1);
       load_b_hi(lb, kc_load);
       mm(fa0, fb0);
       TA::store(An, sa, tid);
-      sched_phase<TN1, NDS, TB1::PIECES - HB, TA::PIECES>();
+      sched_phase<NM1, NDS, TB1::PIECES - HB, TA::PIECES>();
       mm(fa1, fb1);
       TB1::store(An + TA::ELEMS, sb, tid);
-      sched_phase<TN1, 0, 0, TB1::PIECES>();
+      sched_phase<NM1, 0, 0, TB1::PIECES>();
       __syncthreads();
     };
     load_a(xa0, 0);
@@ -443,20 +454,22 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
       iteration(s1 + STAGE, s1, xa1, xb1, xa0, xb0, kc + 3);  // an all-zero chunk when nk is odd
     }
 #pragma unroll
-    for (int j = 0; j < TN1; ++j)
+    for (int i = 0; i < TM1; ++i)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = wn * (RT / 2) + j * 32 + q * 8 + (lane >> 5) * 4;
-        uint2 w;
-        w.x = pack_bf16x2(acc1[j][q * 4 + 0], acc1[j][q * 4 + 1]);
-        w.y = pack_bf16x2(acc1[j][q * 4 + 2], acc1[j][q * 4 + 3]);
-        *reinterpret_cast<uint2*>(Zs + (wm * 32 + (lane & 31)) * L::Z_LD + c) = w;
-      }
+      for (int j = 0; j < TN1; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int c = wn * WN1 + j * 32 + q * 8 + (lane >> 5) * 4;
+          uint2 w;
+          w.x = pack_bf16x2(acc1[i][j][q * 4 + 0], acc1[i][j][q * 4 + 1]);
+          w.y = pack_bf16x2(acc1[i][j][q * 4 + 2], acc1[i][j][q * 4 + 3]);
+          *reinterpret_cast<uint2*>(Zs + (wm * WM1 + i * 32 + (lane & 31)) * L::Z_LD + c) = w;
+        }
   } else if (p.z_splits == 0) {
     const bf16* __restrict__ Z = static_cast<const bf16*>(p.Z);
     constexpr int PPR = RT / 8;
 #pragma unroll
-    for (int i = 0; i < (CH_BM * PPR) / 256; ++i) {
+    for (int i = 0; i < (MB * PPR) / 256; ++i) {
       const int piece = i * 256 + tid;
       const int r = piece / PPR, c = (piece % PPR) * 8;
       uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -470,13 +483,14 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
     // or two trips to memory instead of one per piece.
     const float* __restrict__ Zp = static_cast<const float*>(p.Z);
     constexpr int PPR = RT / 4;
-    constexpr int NP = (CH_BM * PPR) / 256;  // pieces of four floats per thread
+    constexpr int NP = (64 * PPR) / 256;  // pieces of four floats per thread and 64 rows
     constexpr int MAXS = 8, GROUP = 4;
+    for (int h = 0; h < MB / 64; ++h) {  // 64 rows at a time: bounds the registers in flight
     unsigned off[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int piece = i * 256 + tid;
-      const int r = piece / PPR, c = (piece % PPR) * 4;
+      const int r = h * 64 + piece / PPR, c = (piece % PPR) * 4;
       off[i] = c < p.R ? (unsigned)(r * p.R + c) * 4u : OOB_OFFSET;  // rows past M fall outside
     }
     float4 sum[NP];
@@ -507,19 +521,20 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int piece = i * 256 + tid;
-      const int r = piece / PPR, c = (piece % PPR) * 4;
+      const int r = h * 64 + piece / PPR, c = (piece % PPR) * 4;
       uint2 w;
       w.x = pack_bf16x2(sum[i].x, sum[i].y);
       w.y = pack_bf16x2(sum[i].z, sum[i].w);
       *reinterpret_cast<uint2*>(Zs + r * L::Z_LD + c) = w;
     }
+    }  // h
   }
   __syncthreads();  // Zt complete; stage-1 buffers (aliasing Bbuf) are free
 
-  // all 64 rows of Zt, as MFMA fragments, in every wave for the rest of the kernel
-  bf16x8 fa[2][KS];
+  // all rows of Zt, as MFMA fragments, in every wave for the rest of the kernel
+  bf16x8 fa[MT][KS];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fa[i][ks] = read_frag_rowmajor<L::Z_LD>(Zs, i * 32, ks, lane);
 
@@ -529,32 +544,36 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
   bf16* __restrict__ C = static_cast<bf16*>(p.C);
   const float scale = p.scale;
 
-  // One [64 x 128] output tile (wave w owns columns 32 w .. 32 w + 31 of it) from the B2
+  // One [MB x 128] output tile (wave w owns columns 32 w .. 32 w + 31 of it) from the B2
   // tile in `Bs`.  Between its MFMAs go the loads of the tile two ahead (into rl), the
   // next tile's bias (into bvn) and the LDS stores of the next tile (from rs, loaded one
   // step ago, into Bn): issued in one burst, the loads hold every wave at the memory
   // pipe's queue while LDS and MFMA sit idle.
   auto step = [&](int jt, const bf16* Bs, bf16* Bn, const uint2 (&bv)[4], uint2 (&bvn)[4],
                   uint4 (&rl)[TB2::PIECES], uint4 (&rs)[TB2::PIECES]) {
-    f32x16 a0, a1;
+    f32x16 acc[MT];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
     bf16x8 fb = read_frag<B2_KC, TB2::LD>(Bs, wave * 32, 0, lane);
     __builtin_amdgcn_sched_barrier(0);
     load_bias(bvn, jt + 1);
     load_b2(rl, jt + 2);
     // (an LDS store may not pass an LDS read in the compiler's eyes, so each k step's
-    // store sits where the schedule wants it: after the reads of the step that follows)
+    // store sits where the schedule wants it: after the reads of the step that follows;
+    // reading the fragments two steps ahead instead of one measured no faster)
     static_for<0, KS>([&](auto ksc) {
       constexpr int ks = decltype(ksc)::value;
       bf16x8 fbn = fb;
       if (ks + 1 < KS) fbn = read_frag<B2_KC, TB2::LD>(Bs, wave * 32, ks + 1, lane);
-      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[0][ks], a0, 0, 0, 0);
-      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[1][ks], a1, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa[i][ks], acc[i], 0, 0, 0);
       TB2::template store<ks, ks + 1>(Bn, rs, tid);
       fb = fbn;
     });
-    sched_stage2<KS, B2_KC ? 1 : 2>();
+    sched_stage2<KS, B2_KC ? 1 : 2, MT>();
     // Result rows leave straight from registers.  A lane holds, per 8-column group q, the
     // four columns 8 q + 4 (l / 32) .. +3 of its row; exchanging the upper half-wave's part
     // of an even group with the lower half-wave's part of the odd group next to it
@@ -583,8 +602,8 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
           *reinterpret_cast<uint4*>(C + (int64_t)gm * p.ldc + gn) = make_uint4(s0.x, s1.x, s0.y, s1.y);
       }
     };
-    rows_out(a0, 0);
-    rows_out(a1, 32);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) rows_out(acc[i], i * 32);
     __syncthreads();
   };
 
@@ -607,13 +626,19 @@ static hipError_t launch_one(const ChainArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
-static hipError_t launch_small(const ChainArgs& a, hipStream_t s) {
+template <int MB, int RT, bool B2_KC, bool FUSED, bool B1_KC>
+static hipError_t launch_small_mb(const ChainArgs& a, hipStream_t s) {
   const long long grid = (long long)a.tiles_m * a.n_slices;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((chain_small_kernel<RT, B2_KC, FUSED, B1_KC>), dim3((unsigned)grid), dim3(256),
-                     0, s, a);
+  hipLaunchKernelGGL((chain_small_kernel<MB, RT, B2_KC, FUSED, B1_KC>), dim3((unsigned)grid),
+                     dim3(256), 0, s, a);
   return hipGetLastError();
+}
+
+template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
+static hipError_t launch_small(const ChainArgs& a, hipStream_t s) {
+  return a.bm == 128 ? launch_small_mb<128, RT, B2_KC, FUSED, B1_KC>(a, s)
+                     : launch_small_mb<64, RT, B2_KC, FUSED, B1_KC>(a, s);
 }
 
 template <bool B_KC, bool FUSED>
@@ -636,7 +661,9 @@ int chain_bn(int R) { return R <= 128 ? CS_BN : 128; }
 hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s) {
   if (!chain_supported(a.R) || a.n_slices < 1 || (fused && a.R > CHAIN_FUSED_MAX_R))
     return hipErrorInvalidValue;
-  a.tiles_m = (a.M + CH_BM - 1) / CH_BM;
+  if (a.bm == 0) a.bm = CH_BM;
+  if (a.bm != CH_BM && !(a.bm == 128 && a.R <= 128)) return hipErrorInvalidValue;
+  a.tiles_m = (a.M + a.bm - 1) / a.bm;
   if (b_kc) return fused ? launch_rt<true, true>(a, s) : launch_rt<true, false>(a, s);
   return fused ? launch_rt<false, true>(a, s) : launch_rt<false, false>(a, s);
 }

@@ -71,6 +71,7 @@ struct ChainArgs {
   int M, K1, R, N;
   int z_splits;
   int n_slices;        // the N range is cut into this many runs of tiles, one per work-group
+  int bm;              // rows of a token tile: 64 (0 means 64), or 128 for R <= 128
   int tiles_m;         // filled in by the launcher
   float scale;
   // An unrelated split reduction that this launch carries along (narrow-sketch kernels

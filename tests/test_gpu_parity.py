@@ -256,6 +256,42 @@ def test_forced_big_tiles(sk, monkeypatch):
         check_all(sk, w, 2)
 
 
+TALL_CASES = [
+    W.Workload("bf16_ragged", 333, 208, 176, 3, 16, "bf16", seed=4),          # R = 48, ragged last tile
+    W.Workload("bf16_one_token", 1, 64, 48, 1, 16, "bf16", seed=3),
+    W.scaled(W.BERT_BASE_FFN_UP, tokens=1000),                                # R = 128
+    W.scaled(W.BERT_BASE_PROJ[1], tokens=700),                                # R = 64
+    W.Workload("bf16_r128_ragged", 129, 272, 400, 2, 64, "bf16", seed=12),    # one row past a tile
+]
+
+
+@pytest.mark.parametrize("w", TALL_CASES, ids=lambda w: f"{w.name}_T{w.tokens}")
+@pytest.mark.parametrize("plan", [1, 3], ids=["fused", "split_expand"])
+def test_tall_token_tiles_forced(sk, monkeypatch, w, plan):
+    """The 128-row token tiles of the narrow kernels (picked by themselves only from 32768
+    tokens on), forced onto shapes small and ragged enough for a full oracle pass: three
+    calls and the single-call backward."""
+    monkeypatch.setenv("SK_TUNE_BM", "128")
+    check_all(sk, w, plan)
+    sk.sk_set_plan(0)
+    t = W.generate(w)
+    dev = DeviceLayer(t, sk)
+    sk.check(dev.bwd())
+    torch.cuda.synchronize()
+    want = oracle_all(t)
+    for n, got in (("dX", dev.dX), ("dU", dev.dU), ("db", dev.db)):
+        assert rel_err(to_f64(got), want[n]) <= TOL[w.dtype], n
+
+
+def test_tall_token_tiles_by_themselves(sk):
+    """Past 128 x 256 tokens the automatic plan takes the 128-row tiles: a narrow layer at
+    32768 + 77 tokens (ragged last tile), full oracle pass."""
+    w = W.Workload("bf16_many_tokens", 32768 + 77, 128, 384, 2, 32, "bf16", seed=13)
+    check_all(sk, w, 0)
+    w = W.Workload("bf16_many_tokens_r128", 32768 + 1, 96, 256, 2, 64, "bf16", seed=14)
+    check_all(sk, w, 0)
+
+
 def test_bit_reproducible(sk):
     """The token reduction of dU/db runs in a fixed order: two runs agree bit for bit."""
     sk.sk_set_plan(0)
