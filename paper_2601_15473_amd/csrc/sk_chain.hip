@@ -7,7 +7,7 @@
 //     - computed here:  Zt = bf16(A[64 tokens, K1] . B1)            (FUSED), or
 //     - read from the workspace: bf16 [M, R], or the sum of fp32 split-K slabs.
 //
-// A work-group (256 threads, 4 waves) owns one 64-token tile and one slice of the N
+// A work-group (256 threads, 4 waves) owns one token tile and one slice of the N
 // range.  Zt sits in LDS once and every wave lifts the whole of it into registers
 // as MFMA fragments; the waves then split each BN-wide tile of N four ways, so a B2
 // fragment is read from LDS by exactly one wave and used for both 32-row blocks.
@@ -253,15 +253,20 @@ __global__ __launch_bounds__(256) void chain_kernel(const ChainArgs p) {
 
 // ---------------------------------------------------------------------------
 // Narrow sketches (R <= 128): the same chain, shaped for memory-level parallelism.
-// These shapes are bound by bytes, not flops, so the kernel keeps two loads in
-// flight per thread at all times (two register sets, prefetch distance two) and is
-// small enough in LDS and registers for two work-groups per CU.
+// These shapes are bound by bytes and latency, not flops, so the kernel keeps two loads
+// in flight per thread at all times (two register sets, prefetch distance two).
+//   - The token tile is MB = 64 rows, or 128 when the launcher asks for it (many
+//     tokens: half the B2 traffic and LDS reads per MFMA in stage 2).
 //   - stage 1 (waves 2 x 2) walks K1 in 64-wide chunks (x chunk + B1 chunk per step);
 //   - stage 2 takes B2 one whole [R x 128] tile at a time (no k loop inside a tile).
-//     The LDS pipe is the scarce resource here (a 64-lane LDS instruction costs the
-//     CU about 9 cycles, a transposing read twice that per fragment), so the waves
-//     split the tile's columns 1 x 4: every wave holds all 64 rows of Zt in
-//     registers and each B2 fragment is read from LDS exactly once.
+//     A 64-lane LDS instruction costs the CU about 9 cycles, a transposing read
+//     twice that per fragment, so the waves split the tile's columns 1 x 4: every
+//     wave holds all rows of Zt in registers and each B2 fragment is read from LDS
+//     exactly once.  Output rows leave straight from registers.
+//   - In both stages each k step is one scheduling phase: fragment reads of the next
+//     step, the step's MFMAs, a share of the global loads of the chunk / tile two
+//     ahead and of the LDS stores of the next one.  A wave that issues its loads in
+//     one burst waits at the memory pipe's queue while LDS and MFMA idle.
 // ---------------------------------------------------------------------------
 constexpr int CS_BN = 128;
 
