@@ -96,13 +96,49 @@ struct TokenPlan {
   int splits, k_per_split;
 };
 
+// Split count with the least modelled time for one tile shape: rounds of work-groups over
+// the chip x tokens per split x the tile's time per token, plus writing and re-reading one
+// fp32 slab per split.  Rates are measured ones (flop/s one work-group sustains; HBM
+// bytes/s); the model only has to rank the candidates.
+struct SplitChoice {
+  double time;
+  int64_t splits, kps;
+};
+static SplitChoice best_split(int64_t M, int64_t N, int64_t T, int bm, int bn, bool bf16) {
+  const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  const double wg_rate = !bf16 ? 0.3e12 : bm * bn >= 256 * 256 ? 5.0e12
+                         : bm * bn >= 128 * 128 ? 3.5e12 : bm * bn >= 128 * 64 ? 2.2e12 : 1.5e12;
+  const double t_token = 2.0 * bm * bn / wg_rate;
+  const double t_slab = (double)M * N * 8.0 / 4.0e12;
+  int64_t max_splits = (T + 255) / 256;   // at least 256 tokens each
+  if (max_splits > 32) max_splits = 32;
+  SplitChoice c{-1.0, 1, (T + 63) / 64 * 64};
+  for (int64_t sp = 1; sp <= max_splits; ++sp) {
+    int64_t k = (T + sp - 1) / sp;
+    k = (k + 63) / 64 * 64;
+    const int64_t sp_eff = (T + k - 1) / k;
+    const int64_t rounds = (tiles * sp_eff + NUM_CUS - 1) / NUM_CUS;
+    const double t = rounds * k * t_token + (sp_eff > 1 ? sp_eff * t_slab + 2.0e-6 : 0.0);
+    if (c.time < 0.0 || t < c.time) { c.time = t; c.splits = sp_eff; c.kps = k; }
+  }
+  return c;
+}
+
 TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tunable) {
   TokenPlan w{};
   int bm, bn;
   if (dtype == SK_BF16) {
     w.tile = M > 64 ? TILE_128x64 : TILE_64x64;
-    if (((M + 255) / 256) * ((N + 255) / 256) >= NUM_CUS) w.tile = TILE_256x256_W8;
-    else if (((M + 127) / 128) * ((N + 127) / 128) >= NUM_CUS / 2) w.tile = TILE_128x128;  // measured: from half a chip of tiles on, 128 x 128 beats 128 x 64
+    if (((M + 255) / 256) * ((N + 255) / 256) >= NUM_CUS) {
+      w.tile = TILE_256x256_W8;
+    } else if (M > 64) {
+      // 128 x 64 or 128 x 128, whichever the model has finishing first: the narrower
+      // tile fills the chip with fewer token splits (few tokens: c1, c2), the square one
+      // moves fewer bytes per flop (from half a chip of tiles on, or many tokens:
+      // [65536 x 768 -> 3072], R = 128 measured 152 -> 132 us)
+      if (best_split(M, N, T, 128, 128, true).time < best_split(M, N, T, 128, 64, true).time)
+        w.tile = TILE_128x128;
+    }
     if (const char* e = tunable ? getenv("SK_TUNE_WTILE") : nullptr) {  // tuning experiments only
       const int t = atoi(e);
       if (t >= 0 && t < TILE_COUNT) w.tile = t;
@@ -113,27 +149,10 @@ TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tuna
     w.tile = -1;
     bm = F32_BM; bn = F32_BN;
   }
-  const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-  // Pick the split count with the least modelled time: rounds of work-groups over the
-  // chip x tokens per split x the tile's time per token, plus writing and re-reading one
-  // fp32 slab per split.  Rates are measured ones (flop/s one work-group sustains; HBM
-  // bytes/s); the model only has to rank the candidates.
-  const double wg_rate = dtype != SK_BF16 ? 0.3e12 : bm * bn >= 256 * 256 ? 5.0e12
-                         : bm * bn >= 128 * 128 ? 3.5e12 : bm * bn >= 128 * 64 ? 2.2e12 : 1.5e12;
-  const double t_token = 2.0 * bm * bn / wg_rate;
-  const double t_slab = (double)M * N * 8.0 / 4.0e12;
-  int64_t max_splits = (T + 255) / 256;   // at least 256 tokens each
+  const SplitChoice c = best_split(M, N, T, bm, bn, dtype == SK_BF16);
+  int64_t splits = c.splits, kps = c.kps;
+  int64_t max_splits = (T + 255) / 256;
   if (max_splits > 32) max_splits = 32;
-  int64_t splits = 1, kps = (T + 63) / 64 * 64;
-  double best = -1.0;
-  for (int64_t sp = 1; sp <= max_splits; ++sp) {
-    int64_t k = (T + sp - 1) / sp;
-    k = (k + 63) / 64 * 64;
-    const int64_t sp_eff = (T + k - 1) / k;
-    const int64_t rounds = (tiles * sp_eff + NUM_CUS - 1) / NUM_CUS;
-    const double t = rounds * k * t_token + (sp_eff > 1 ? sp_eff * t_slab + 2.0e-6 : 0.0);
-    if (best < 0.0 || t < best) { best = t; splits = sp_eff; kps = k; }
-  }
   if (const char* e = tunable ? getenv("SK_TUNE_WSPLITS") : nullptr) {  // tuning experiments only
     splits = atoi(e) < 1 ? 1 : (atoi(e) > max_splits ? max_splits : atoi(e));
     kps = ((T + splits - 1) / splits + 63) / 64 * 64;
