@@ -208,6 +208,32 @@ enum Plan : int {
                           // sums them on the way into LDS (bf16, R <= 512)
 };
 
+// Shape of the expand/fused launch: rows of a token tile and the number of N slices (one
+// work-group per CU).
+struct ChainShape {
+  int bm, slices;
+};
+ChainShape chain_shape(int64_t T, int64_t N, int R) {
+  ChainShape c;
+  // 128-row token tiles halve the B2 traffic and the LDS reads per MFMA of stage 2; they
+  // pay once their tiles alone fill the chip (measured on [T x 768 -> 3072], R = 128:
+  // forward -14..16 % from 65536 tokens on, +17 % at 4096 tokens, where they double the
+  // number of work-groups that repeat stage 1)
+  c.bm = (R <= 128 && T >= 128 * (int64_t)NUM_CUS) ? 128 : 64;
+  if (const char* e = getenv("SK_TUNE_BM")) {  // tuning experiments and tests only
+    const int v = atoi(e);
+    if (v == 64 || (v == 128 && R <= 128)) c.bm = v;
+  }
+  const int64_t tiles_m = (T + c.bm - 1) / c.bm;
+  const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
+  int64_t sl = NUM_CUS / tiles_m;
+  if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
+  if (sl > n_tiles) sl = n_tiles;
+  if (sl < 1) sl = 1;
+  c.slices = (int)sl;
+  return c;
+}
+
 Plan pick_plan(const Shape& s, sk_op op) {
   const int forced = g_plan.load(std::memory_order_relaxed);
   const bool chain_ok = s.dtype == SK_BF16 && chain_supported(s.R);
@@ -221,12 +247,15 @@ Plan pick_plan(const Shape& s, sk_op op) {
   // automatic (measured on MI355X): the on-chip plans win while the sketch is narrow
   // (R <= 128: the layer is bound by bytes and by launch count); wider sketches run
   // faster as two general GEMMs with large tiles.  One fused kernel recomputes the first
-  // contraction once per N slice, which is cheap while that contraction is short (up to
-  // about 1500 long: the forward of an up-projection, either call of a square layer);
-  // a long one (the input gradient of an up-projection runs over `out`) is split instead.
+  // contraction once per N slice, which is cheap while length x slices stays small: up to
+  // about 6000 (the forward of an up-projection at 4096 tokens: 768 x 4; its input
+  // gradient, 3072 long, from two slices down, i.e. from 6144 tokens on, where it
+  // measured level at two slices and 16-20 % ahead at one).  Beyond that the first
+  // contraction is split over its length instead and the expansion sums the slabs.
   if (chain_ok && s.R <= 128) {
     const int64_t k1 = op == SK_OP_FWD ? s.in : s.out;
-    return k1 <= 1536 ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
+    const int64_t n2 = op == SK_OP_FWD ? s.out : s.in;
+    return k1 * chain_shape(s.T, n2, s.R).slices <= 6144 ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
   }
   return PLAN_TWO_GEMM;
 }
@@ -257,32 +286,6 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
   q.k_per_split = (int)kps;
   q.bytes = splits > 1 ? align_up((size_t)splits * s.T * s.R * 4) : align_up((size_t)s.T * s.R * 2);
   return q;
-}
-
-// Shape of the expand/fused launch: rows of a token tile and the number of N slices (one
-// work-group per CU).
-struct ChainShape {
-  int bm, slices;
-};
-ChainShape chain_shape(int64_t T, int64_t N, int R) {
-  ChainShape c;
-  // 128-row token tiles halve the B2 traffic and the LDS reads per MFMA of stage 2; they
-  // pay once their tiles alone fill the chip (measured on [T x 768 -> 3072], R = 128:
-  // forward -14..16 % from 65536 tokens on, +17 % at 4096 tokens, where they double the
-  // number of work-groups that repeat stage 1)
-  c.bm = (R <= 128 && T >= 128 * (int64_t)NUM_CUS) ? 128 : 64;
-  if (const char* e = getenv("SK_TUNE_BM")) {  // tuning experiments and tests only
-    const int v = atoi(e);
-    if (v == 64 || (v == 128 && R <= 128)) c.bm = v;
-  }
-  const int64_t tiles_m = (T + c.bm - 1) / c.bm;
-  const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
-  int64_t sl = NUM_CUS / tiles_m;
-  if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
-  if (sl > n_tiles) sl = n_tiles;
-  if (sl < 1) sl = 1;
-  c.slices = (int)sl;
-  return c;
 }
 
 // Workspace of the first-stage gradient for nc columns: G = dY . U_sub^T [T, nc] in the
