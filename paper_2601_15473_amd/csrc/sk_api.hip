@@ -271,10 +271,15 @@ struct SketchPlan {
 SketchPlan plan_sketch(const Shape& s, int64_t K) {
   SketchPlan q{};
   q.tile = s.R <= 64 ? TILE_64x64 : (s.R <= 256 ? TILE_64x128 : TILE_128x128);
+  if (const char* e = getenv("SK_TUNE_STILE")) {  // tuning experiments only
+    const int t = atoi(e);
+    if (t == TILE_64x64 || t == TILE_64x128 || t == TILE_128x128 || t == TILE_128x64) q.tile = t;
+  }
   int bm, bn;
   tile_dims(q.tile, bm, bn);
   const int64_t tiles = ((s.T + bm - 1) / bm) * ((s.R + bn - 1) / bn);
   int64_t splits = (NUM_CUS + tiles - 1) / tiles;
+  if (const char* e = getenv("SK_TUNE_SSPLITS")) splits = atoi(e);  // tuning experiments only (clamped below)
   const int64_t max_splits = K / 128 > 0 ? K / 128 : 1;   // at least two k chunks each
   if (splits > max_splits) splits = max_splits;
   if (splits > 8) splits = 8;
