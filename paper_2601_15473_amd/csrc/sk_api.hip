@@ -82,8 +82,11 @@ struct WeightPlan {
   bool own_colsum;     // db from its own kernel (the big tile has no registers for it)
   int colsum_splits;   // rows of column-sum partials: `splits`, or the own kernel's row runs
   int colsum_rows;     // tokens per row run of the own kernel
-  size_t z_bytes, part_bytes, csum_bytes;
-  size_t total() const { return z_bytes + part_bytes + csum_bytes; }
+  int z_tile;          // bf16: tile of the GEMM that recomputes Z^T
+  int z_splits;        // split of that GEMM over `in` (fp32 slabs, summed into bf16 Z^T)
+  int z_k_per_split;
+  size_t z_bytes, part_bytes, csum_bytes, zpart_bytes;
+  size_t total() const { return z_bytes + part_bytes + csum_bytes + zpart_bytes; }
 };
 
 // A contraction over the token axis with a small fp32 output [M, N] (a weight gradient):
@@ -169,12 +172,33 @@ WeightPlan plan_weight(const Shape& s) {
   const TokenPlan t = plan_tokens(s.R, s.out, s.T, s.dtype, true);
   w.tile = t.tile;
   w.own_colsum = t.big_tile;
+  w.z_splits = 1;
+  w.z_k_per_split = (int)s.in;
   if (s.dtype == SK_BF16) {
     w.ldz = (s.T + 63) / 64 * 64;
     w.z_bytes = align_up((size_t)s.R * w.ldz * 2);
+    // Z^T [R, T] has few tiles when the sketch is narrow or the tokens few; over a long
+    // `in` (the paper's 8192-wide layers: 64 tiles of 64 x 64 walking 128 chunks each,
+    // 51 us) it is split over `in` into fp32 slabs that one small kernel sums into the
+    // bf16 operand: ranges at least 1024 long, as many as still fit the chip.
+    w.z_tile = choose_tile(s.R, s.T, s.in, 1);
+    int bm, bn;
+    tile_dims(w.z_tile, bm, bn);
+    const int64_t tiles = ((s.R + bm - 1) / bm) * ((s.T + bn - 1) / bn);
+    int64_t zs = NUM_CUS / tiles;
+    if (zs > s.in / 1024) zs = s.in / 1024;
+    if (zs > 8) zs = 8;
+    if (zs >= 2) {
+      int64_t kps = (s.in + zs - 1) / zs;
+      kps = (kps + 63) / 64 * 64;
+      w.z_splits = (int)((s.in + kps - 1) / kps);
+      w.z_k_per_split = (int)kps;
+    }
+    w.zpart_bytes = w.z_splits > 1 ? align_up((size_t)w.z_splits * s.R * w.ldz * 4) : 0;
   } else {
     w.ldz = s.R;
     w.z_bytes = align_up((size_t)s.T * s.R * 4);
+    w.z_tile = -1;
   }
   const int64_t splits = t.splits, kps = t.k_per_split;
   w.splits = (int)splits;
@@ -213,7 +237,7 @@ enum Plan : int {
 struct ChainShape {
   int bm, slices;
 };
-ChainShape chain_shape(int64_t T, int64_t N, int R) {
+ChainShape chain_shape(int64_t T, int64_t N, int R, bool share_cu) {
   ChainShape c;
   // 128-row token tiles halve the B2 traffic and the LDS reads per MFMA of stage 2; they
   // pay once their tiles alone fill the chip (measured on [T x 768 -> 3072], R = 128:
@@ -227,6 +251,10 @@ ChainShape chain_shape(int64_t T, int64_t N, int R) {
   const int64_t tiles_m = (T + c.bm - 1) / c.bm;
   const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
   int64_t sl = NUM_CUS / tiles_m;
+  // share_cu: the expansion alone (no first contraction to repeat per slice, no carried
+  // reduction to deal out) of a sketch up to 64 wide is small enough in LDS for two
+  // work-groups per CU (8192-wide layer, R = 16: input gradient 39.8 -> 33.5 us)
+  if (share_cu && R <= 64) sl = 2 * NUM_CUS / tiles_m;
   if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
@@ -255,7 +283,7 @@ Plan pick_plan(const Shape& s, sk_op op) {
   if (chain_ok && s.R <= 128) {
     const int64_t k1 = op == SK_OP_FWD ? s.in : s.out;
     const int64_t n2 = op == SK_OP_FWD ? s.out : s.in;
-    return k1 * chain_shape(s.T, n2, s.R).slices <= 6144 ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
+    return k1 * chain_shape(s.T, n2, s.R, false).slices <= 6144 ? PLAN_FUSED : PLAN_SPLIT_EXPAND;
   }
   return PLAN_TWO_GEMM;
 }
@@ -278,7 +306,11 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
   int bm, bn;
   tile_dims(q.tile, bm, bn);
   const int64_t tiles = ((s.T + bm - 1) / bm) * ((s.R + bn - 1) / bn);
-  int64_t splits = (NUM_CUS + tiles - 1) / tiles;
+  // one work-group per CU; two for the 64 x 64 tile (R <= 64), whose work-groups are small
+  // enough to share a CU and, streaming a long x from HBM, need the loads in flight of
+  // two (8192-wide layer, R = 16: forward 36.8 -> 33.5 us)
+  const int64_t want = s.R <= 64 ? 2 * NUM_CUS : NUM_CUS;
+  int64_t splits = (want + tiles - 1) / tiles;
   if (const char* e = getenv("SK_TUNE_SSPLITS")) splits = atoi(e);  // tuning experiments only (clamped below)
   const int64_t max_splits = K / 128 > 0 ? K / 128 : 1;   // at least two k chunks each
   if (splits > max_splits) splits = max_splits;
@@ -404,7 +436,7 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
     c.A = x; c.B1 = S_cat; c.B2 = U_cat; c.bias = bias; c.C = y;
     c.lda = in; c.ldb1 = s.R; c.ldb2 = out; c.ldc = out;
     c.M = (int)tokens; c.K1 = (int)in; c.R = s.R; c.N = (int)out; c.scale = scale;
-    { const ChainShape cs = chain_shape(tokens, out, s.R); c.n_slices = cs.slices; c.bm = cs.bm; }
+    { const ChainShape cs = chain_shape(tokens, out, s.R, plan != PLAN_FUSED); c.n_slices = cs.slices; c.bm = cs.bm; }
     if (plan == PLAN_SPLIT_EXPAND) {
       const SketchPlan q = plan_sketch(s, in);
       GemmArgs a = dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr);
@@ -448,7 +480,7 @@ sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_c
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-    { const ChainShape cs = chain_shape(tokens, in, s.R); c.n_slices = cs.slices; c.bm = cs.bm; }
+    { const ChainShape cs = chain_shape(tokens, in, s.R, plan != PLAN_FUSED); c.n_slices = cs.slices; c.bm = cs.bm; }
     if (plan == PLAN_SPLIT_EXPAND) {
       const SketchPlan q = plan_sketch(s, out);
       GemmArgs a = dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr);
@@ -498,7 +530,14 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
   if (s.dtype == SK_BF16) {
     GemmArgs z = dense_args(S_cat, s.R, x, in, Z, w.ldz, s.R, tokens, in, 1.0f, nullptr);
     z.n_store = (int)w.ldz;
-    e = launch_gemm_bf16(GEMM_TT, choose_tile(s.R, tokens, in, 1), z, hs);
+    if (w.z_splits > 1) {
+      float* zpart = reinterpret_cast<float*>(ws + w.z_bytes + w.part_bytes + w.csum_bytes);
+      z.C = zpart; z.splits = w.z_splits; z.k_per_split = w.z_k_per_split;
+      e = launch_gemm_bf16(GEMM_TT_F32, w.z_tile, z, hs);
+      if (e == hipSuccess) e = launch_reduce_to_bf16(zpart, Z, (int64_t)s.R * w.ldz, w.z_splits, hs);
+    } else {
+      e = launch_gemm_bf16(GEMM_TT, w.z_tile, z, hs);
+    }
     a.A = Z; a.lda = w.ldz;
   } else {
     e = launch_gemm_f32(GEMM_NN, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
@@ -562,8 +601,9 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
   // benchmark configurations (bf16; the dual kernel is built for a few tile pairs only);
   // everything else runs the two gradients one after the other.
   const WeightPlan w = plan_weight(s);
+  // (not when Z^T is recomputed in split form: that is four launches of its own)
   const bool bf16_auto = s.dtype == SK_BF16 && g_plan.load(std::memory_order_relaxed) == PLAN_AUTO &&
-                         !w.own_colsum;
+                         !w.own_colsum && w.z_splits == 1;
   const Plan in_plan = pick_plan(s, SK_OP_BWD_INPUT);
   const int z_tile = bf16_auto ? choose_tile(s.R, tokens, in, 1) : -1;
   const GemmKind du_kind = GEMM_NN_F32_COLSUM;
@@ -602,7 +642,7 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
     c.A = dY; c.B1 = U_cat; c.B2 = S_cat; c.bias = nullptr; c.C = dX;
     c.lda = out; c.ldb1 = out; c.ldb2 = s.R; c.ldc = in;
     c.M = (int)tokens; c.K1 = (int)out; c.R = s.R; c.N = (int)in; c.scale = scale;
-    { const ChainShape cs = chain_shape(tokens, in, s.R); c.n_slices = cs.slices; c.bm = cs.bm; }
+    { const ChainShape cs = chain_shape(tokens, in, s.R, false); c.n_slices = cs.slices; c.bm = cs.bm; }
     c.Z = ws_in; c.z_splits = q.splits; c.z_slab = (int64_t)tokens * s.R;
     // Z^T.dY, then the expansion of dX carrying the sum of the token splits
     e = launch_gemm_bf16(du_kind, w.tile, du, hs);

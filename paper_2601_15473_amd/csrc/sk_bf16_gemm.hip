@@ -329,6 +329,25 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const ReduceArgs p) 
   *reinterpret_cast<float4*>(out + i4) = s;
 }
 
+// Sum of split-K slabs in index order, rounded once to bf16 (an intermediate that the
+// next GEMM reads as an operand).
+__global__ __launch_bounds__(256) void reduce_to_bf16_kernel(const float* __restrict__ part,
+                                                             bf16* __restrict__ out, int64_t n,
+                                                             int splits) {
+  const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 >= n) return;
+  float4 s = *reinterpret_cast<const float4*>(part + i4);
+#pragma unroll 8
+  for (int k = 1; k < splits; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + i4);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  uint2 w;
+  w.x = pack_bf16x2(s.x, s.y);
+  w.y = pack_bf16x2(s.z, s.w);
+  *reinterpret_cast<uint2*>(out + i4) = w;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
 static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   a.tiles_m = (a.M + BM - 1) / BM;
@@ -369,6 +388,7 @@ hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStrea
     case GEMM_TT: return launch_tiles<false, true, bf16, false>(tile, a, s);
     case GEMM_NN_F32_COLSUM: return launch_tiles<true, false, float, true>(tile, a, s);
     case GEMM_NT_F32: return launch_tiles<true, true, float, false>(tile, a, s);
+    case GEMM_TT_F32: return launch_tiles<false, true, float, false>(tile, a, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -478,6 +498,15 @@ hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, in
   const dim3 grid((unsigned)((cols + COLSUM_COLS - 1) / COLSUM_COLS), (unsigned)splits);
   hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(256), 0, s,
                      static_cast<const unsigned short*>(in), out, rows, cols, rows_per_split);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_to_bf16(const float* part, void* out, int64_t n, int splits, hipStream_t s) {
+  if (n <= 0 || (n & 3) != 0 || splits < 1) return hipErrorInvalidValue;
+  const int64_t groups = (n / 4 + 255) / 256;
+  if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(reduce_to_bf16_kernel, dim3((unsigned)groups), dim3(256), 0, s, part,
+                     static_cast<bf16*>(out), n, splits);
   return hipGetLastError();
 }
 

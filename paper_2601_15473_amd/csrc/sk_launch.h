@@ -13,6 +13,7 @@ enum GemmKind : int {
   GEMM_TT = 5,      // A [K,M], B [N,K]            -> storage type
   GEMM_NN_F32_COLSUM = 6,  // as GEMM_NN_F32, plus the column sums of B
   GEMM_TN_F32_PLAIN = 7,   // as GEMM_TN_F32 without the column sums (any tile)
+  GEMM_TT_F32 = 8,         // as GEMM_TT, split-K          -> fp32 slabs
 };
 
 enum TileCfg : int {
@@ -41,6 +42,9 @@ hipError_t launch_gemm_f32(GemmKind kind, const GemmArgs& a, hipStream_t s);
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16;
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s);
+// out[i] = bf16(sum over s of part[s][i]), i < n (n a multiple of 4; slabs n elements apart,
+// summed in index order)
+hipError_t launch_reduce_to_bf16(const float* part, void* out, int64_t n, int splits, hipStream_t s);
 // Two GEMMs that do not depend on each other in one launch (see dual_gemm_kernel); built
 // for a few (kind, tile) pairs only -- ask dual_gemm_supported first.  `a` should be the
 // longer-running one.
