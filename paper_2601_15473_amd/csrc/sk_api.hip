@@ -74,6 +74,57 @@ int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
   return TILE_64x64;
 }
 
+// A first contraction of the layer run as a general GEMM: bf16 [M, N] result (the narrow
+// intermediate, or its transpose), contraction length K.  Over a long K a small output
+// leaves the choice between small tiles that fill the chip unsplit and large tiles split
+// over K into fp32 slabs, which one more small kernel sums into the bf16 result.  The same
+// rates as the token-split model rank the two (per work-group flop/s by tile; slabs written
+// and re-read at 4 TB/s; 5 us for the extra launch), and the split form has to win by a
+// fifth to be taken.  8192-wide layer, R = 256, 4096 tokens: 54 us unsplit on 64 x 64 tiles.
+struct FirstPlan {
+  int tile, splits, k_per_split;
+  size_t slab_bytes;   // fp32 slabs (0 when not split)
+};
+FirstPlan plan_first(int64_t M, int64_t N, int64_t K) {
+  FirstPlan f{};
+  f.tile = choose_tile(M, N, K, 1);
+  f.splits = 1;
+  f.k_per_split = (int)((K + 63) / 64 * 64);
+  f.slab_bytes = 0;
+  auto rate = [](int bm, int bn) {
+    return bm * bn >= 256 * 256 ? 5.0e12 : bm * bn >= 128 * 128 ? 3.5e12 : bm * bn >= 128 * 64 ? 2.2e12 : 1.5e12;
+  };
+  auto time_of = [&](int tile, int64_t splits, int64_t kps) {
+    int bm, bn;
+    tile_dims(tile, bm, bn);
+    const int64_t wgs = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * splits;
+    const int64_t rounds = (wgs + NUM_CUS - 1) / NUM_CUS;
+    double t = rounds * (double)kps * 2.0 * bm * bn / rate(bm, bn);
+    if (splits > 1) t += splits * (double)M * N * 8.0 / 4.0e12 + 5.0e-6;
+    return t;
+  };
+  if (getenv("SK_TUNE_TILE")) return f;  // a forced tile is taken as it is
+  const double t_plain = time_of(f.tile, 1, K);
+  double best = t_plain * 0.8;
+  static const int cand[] = {TILE_128x128, TILE_128x64, TILE_64x128};
+  for (int c = 0; c < 3; ++c) {
+    int bm, bn;
+    tile_dims(cand[c], bm, bn);
+    if (bm > (M + 63) / 64 * 64 || bn > (N + 63) / 64 * 64) continue;
+    for (int64_t sp = 2; sp <= 8; ++sp) {
+      int64_t kps = (K + sp - 1) / sp;
+      kps = (kps + 63) / 64 * 64;
+      if (kps < 512) break;
+      const int64_t sp_eff = (K + kps - 1) / kps;
+      if (sp_eff < 2) continue;
+      const double t = time_of(cand[c], sp_eff, kps);
+      if (t < best) { best = t; f.tile = cand[c]; f.splits = (int)sp_eff; f.k_per_split = (int)kps; }
+    }
+  }
+  if (f.splits > 1) f.slab_bytes = align_up((size_t)f.splits * M * N * 4);
+  return f;
+}
+
 struct WeightPlan {
   int tile;
   int splits;
@@ -177,23 +228,13 @@ WeightPlan plan_weight(const Shape& s) {
   if (s.dtype == SK_BF16) {
     w.ldz = (s.T + 63) / 64 * 64;
     w.z_bytes = align_up((size_t)s.R * w.ldz * 2);
-    // Z^T [R, T] has few tiles when the sketch is narrow or the tokens few; over a long
-    // `in` (the paper's 8192-wide layers: 64 tiles of 64 x 64 walking 128 chunks each,
-    // 51 us) it is split over `in` into fp32 slabs that one small kernel sums into the
-    // bf16 operand: ranges at least 1024 long, as many as still fit the chip.
-    w.z_tile = choose_tile(s.R, s.T, s.in, 1);
-    int bm, bn;
-    tile_dims(w.z_tile, bm, bn);
-    const int64_t tiles = ((s.R + bm - 1) / bm) * ((s.T + bn - 1) / bn);
-    int64_t zs = NUM_CUS / tiles;
-    if (zs > s.in / 1024) zs = s.in / 1024;
-    if (zs > 8) zs = 8;
-    if (zs >= 2) {
-      int64_t kps = (s.in + zs - 1) / zs;
-      kps = (kps + 63) / 64 * 64;
-      w.z_splits = (int)((s.in + kps - 1) / kps);
-      w.z_k_per_split = (int)kps;
-    }
+    // Z^T [R, T] recomputed as a general GEMM over `in` (plan_first: split over a long
+    // `in` when its tiles are few -- the paper's 8192-wide layers at R = 16: 64 tiles of
+    // 64 x 64 walking 128 chunks each took 51 us, four ranges and the sum take 17)
+    const FirstPlan f = plan_first(s.R, s.T, s.in);
+    w.z_tile = f.tile;
+    w.z_splits = f.splits;
+    w.z_k_per_split = f.k_per_split;
     w.zpart_bytes = w.z_splits > 1 ? align_up((size_t)w.z_splits * s.R * w.ldz * 4) : 0;
   } else {
     w.ldz = s.R;
@@ -340,6 +381,8 @@ size_t workspace_for(sk_op op, const Shape& s) {
     case SK_OP_BWD_INPUT: {
       // the maximum over the plans, so one buffer serves whichever is selected
       size_t need = mid;
+      if (s.dtype == SK_BF16)   // two GEMMs with the first one split: slabs behind the intermediate
+        need += plan_first(s.T, s.R, op == SK_OP_FWD ? s.in : s.out).slab_bytes;
       if (s.dtype == SK_BF16 && chain_supported(s.R)) {
         const size_t b = plan_sketch(s, op == SK_OP_FWD ? s.in : s.out).bytes;
         if (b > need) need = b;
@@ -367,6 +410,20 @@ size_t workspace_for(sk_op op, const Shape& s) {
 hipError_t gemm(const Shape& s, GemmKind kind, GemmArgs a, hipStream_t st) {
   if (s.dtype == SK_BF16) return launch_gemm_bf16(kind, choose_tile(a.M, a.N, a.K, 1), a, st);
   return launch_gemm_f32(kind, a, st);
+}
+
+// The first of the two GEMMs of a call: as it is, or (bf16, plan_first) split over its
+// contraction into fp32 slabs at `slabs` that are then summed into the bf16 result a.C.
+hipError_t first_gemm(const Shape& s, GemmKind kind, GemmKind kind_slabs, GemmArgs a, void* slabs,
+                      hipStream_t st) {
+  if (s.dtype != SK_BF16) return launch_gemm_f32(kind, a, st);
+  const FirstPlan f = plan_first(a.M, a.N, a.K);
+  if (f.splits == 1) return launch_gemm_bf16(kind, f.tile, a, st);
+  void* out = a.C;
+  a.C = slabs; a.splits = f.splits; a.k_per_split = f.k_per_split;
+  const hipError_t e = launch_gemm_bf16(kind_slabs, f.tile, a, st);
+  if (e != hipSuccess) return e;
+  return launch_reduce_to_bf16(static_cast<const float*>(slabs), out, (int64_t)a.M * a.N, f.splits, st);
 }
 
 // C[M,N] = scale * (A[M,K] . B) + bias through the workspace-free single GEMM.
@@ -450,7 +507,9 @@ sk_status sk_linear_fwd(const void* x, const void* S_cat, const void* U_cat, con
   }
   // Z = x . S_cat, then y = scale * Z . U_cat + bias
   hipError_t e;
-  e = gemm(s, GEMM_NN, dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+  e = first_gemm(s, GEMM_NN, GEMM_NN_F32,
+                 dense_args(x, in, S_cat, s.R, workspace, s.R, tokens, s.R, in, 1.0f, nullptr),
+                 static_cast<unsigned char*>(workspace) + align_up((size_t)tokens * s.R * s.esize), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (x.S)");
   e = gemm(s, GEMM_NN, dense_args(workspace, s.R, U_cat, out, y, out, tokens, out, s.R, scale, bias), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_fwd (Z.U)");
@@ -493,7 +552,9 @@ sk_status sk_linear_bwd_input(const void* dY, const void* S_cat, const void* U_c
     return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd_input (expand)");
   }
   // G = dY . U_cat^T (U_cat read as [N = R, K = out]), then dX = scale * G . S_cat^T
-  hipError_t e = gemm(s, GEMM_NT, dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr), hs);
+  hipError_t e = first_gemm(s, GEMM_NT, GEMM_NT_F32,
+                            dense_args(dY, out, U_cat, out, workspace, s.R, tokens, s.R, out, 1.0f, nullptr),
+                            static_cast<unsigned char*>(workspace) + align_up((size_t)tokens * s.R * s.esize), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_input (dY.U^T)");
   e = gemm(s, GEMM_NT, dense_args(workspace, s.R, S_cat, s.R, dX, in, tokens, in, s.R, scale, nullptr), hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_input (G.S^T)");
@@ -659,7 +720,8 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
   // eight-wave tile on its own: that one leaves no room on a CU to share (measured at
   // BERT-large: 125 us shared against 133 us one after the other)
   if (dx_tile == TILE_256x256_W8) dx_tile = TILE_128x128;
-  if (bf16_auto && in_plan == PLAN_TWO_GEMM && dual_gemm_supported(GEMM_NT, g_tile, GEMM_TT, z_tile) &&
+  if (bf16_auto && in_plan == PLAN_TWO_GEMM && plan_first(tokens, s.R, out).splits == 1 &&
+      dual_gemm_supported(GEMM_NT, g_tile, GEMM_TT, z_tile) &&
       dual_gemm_supported(du_kind, w.tile, GEMM_NT, dx_tile)) {
     g_hip_error.clear();
     const GemmArgs g = dense_args(dY, out, U_cat, out, ws_in, s.R, tokens, s.R, out, 1.0f, nullptr);
