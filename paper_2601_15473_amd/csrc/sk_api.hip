@@ -80,7 +80,8 @@ int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
 // over K into fp32 slabs, which one more small kernel sums into the bf16 result.  The same
 // rates as the token-split model rank the two (per work-group flop/s by tile; slabs written
 // and re-read at 4 TB/s; 5 us for the extra launch), and the split form has to win by a
-// fifth to be taken.  8192-wide layer, R = 256, 4096 tokens: 54 us unsplit on 64 x 64 tiles.
+// tenth to be taken (measured on the 8192-wide layers: modelled ratios of 0.85 paid, 0.95
+// did not).  8192-wide layer, R = 256, 4096 tokens: 54 us unsplit on 64 x 64 tiles.
 struct FirstPlan {
   int tile, splits, k_per_split;
   size_t slab_bytes;   // fp32 slabs (0 when not split)
@@ -105,7 +106,7 @@ FirstPlan plan_first(int64_t M, int64_t N, int64_t K) {
   };
   if (getenv("SK_TUNE_TILE")) return f;  // a forced tile is taken as it is
   const double t_plain = time_of(f.tile, 1, K);
-  double best = t_plain * 0.8;
+  double best = t_plain * 0.9;
   static const int cand[] = {TILE_128x128, TILE_128x64, TILE_64x128};
   for (int c = 0; c < 3; ++c) {
     int bm, bn;
