@@ -65,6 +65,11 @@ SMALL = [
     # the paper's own grid (square 8192 layers); l = 3 makes the 1/l scale inexact
     W.scaled(W.BY_NAME["grid8192_l3_k16"], tokens=200),
     W.scaled(W.BY_NAME["grid8192_l3_k512"], tokens=200),
+    # long, ragged contractions (not multiples of the 64-wide k chunk): the first GEMM of a
+    # call and the recomputation of Z^T split over them into fp32 slabs
+    W.Workload("bf16_long_in_ragged", 300, 2064, 176, 2, 24, "bf16", seed=20),
+    W.Workload("bf16_long_out_ragged", 300, 176, 2064, 2, 24, "bf16", seed=21),
+    W.Workload("bf16_long_both_r272", 260, 2064, 2064, 2, 136, "bf16", seed=22),
 ]
 
 
@@ -173,6 +178,8 @@ def test_outputs_past_two_gib_sampled(sk):
 
 
 BWD_CASES = [
+    W.Workload("bf16_long_both_r272", 260, 2064, 2064, 2, 136, "bf16", seed=22),   # split first GEMMs: no shared launches
+    W.scaled(W.BY_NAME["grid8192_l1_k16"], tokens=300),                             # split Z^T recomputation
     W.scaled(W.BERT_BASE_FFN_UP, tokens=1000),        # shared launches (R = 128, long first contraction)
     W.BERT_BASE_FFN_UP,
     W.scaled(W.BERT_BASE_PROJ[0], tokens=700),        # R = 32: 64 x 64 tiles
