@@ -126,7 +126,7 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
   }
 
   // Iteration shape (PF == 1): the global loads of chunk kc + 1 are issued during k
-  // steps 0 and 1 of chunk kc and stored to the other LDS buffer during k step 3.
+  // step 0 of chunk kc and stored to the other LDS buffer during k step 3.
   // Chunks past the end of the k range load as zeros: no branch around any load.
   if (PF == 1) {
     uint4 ra[TA::PIECES], rb[TB::PIECES];
@@ -156,7 +156,10 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
       read(As, 3, fa1, fb1);
       mma(fa0, fb0);
       sched_phase<NMMA, NDSR, 0, 0>();
-      // k step 3: MFMAs + LDS stores of the next chunk
+      // k step 3: MFMAs + LDS stores of the next chunk.  (Stores and barrier one step
+      // earlier, with the next chunk's first fragments read behind this step's MFMAs as
+      // the small tiles do below, cost the eight-wave tile 5 %: its loads then have
+      // two k steps to land instead of three, and the extra live fragments spill.)
       mma(fa1, fb1);
       TA::store(An, ra, tid);
       TB::store(An + TA::ELEMS, rb, tid);
@@ -181,7 +184,6 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
       // loads into (la, lb) for chunk k0, A's during k step 0 and B's during k step 1 (in
       // one burst they hold the waves at the memory pipe's queue; measured 1 % on the
       // [8192 x 1024..4096] shapes); stores from (sa, sb), loaded an iteration ago
-      read(As, 0, fa0, fb0);
       __builtin_amdgcn_sched_barrier(0);
       read(As, 1, fa1, fb1);
       TA::load(la, A, p.lda, m0, p.M, k0, k_end, p.K, tid);
@@ -190,16 +192,20 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
       read(As, 2, fa0, fb0);
       TB::load(lb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
       mma(fa1, fb1);
-      sched_phase<NMMA, NDSR, TB::PIECES, 0>();
+      TA::store(An, sa, tid);
+      sched_phase<NMMA, NDSR, TB::PIECES, TA::PIECES>();
       read(As, 3, fa1, fb1);
       mma(fa0, fb0);
-      TA::store(An, sa, tid);
-      sched_phase<NMMA, NDSR, 0, TA::PIECES>();
-      mma(fa1, fb1);
       TB::store(An + TA::ELEMS, sb, tid);
-      sched_phase<NMMA, 0, 0, TB::PIECES>();
+      sched_phase<NMMA, NDSR, 0, TB::PIECES>();
+      // the barrier one k step before the end of the chunk: the first fragments of the
+      // next chunk come in behind the last step's MFMAs, not behind the barrier
       __syncthreads();
+      read(An, 0, fa0, fb0);
+      mma(fa1, fb1);
+      sched_phase<NMMA, NDSR, 0, 0>();
     };
+    read(lds, 0, fa0, fb0);
     for (int kc = 0; kc < nk; kc += 2) {
       iteration(lds, lds + STAGE, ra0, rb0, ra1, rb1, k_begin + (kc + 2) * BK);
       // an all-zero chunk when nk is odd
