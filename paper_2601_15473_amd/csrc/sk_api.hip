@@ -297,6 +297,11 @@ ChainShape chain_shape(int64_t T, int64_t N, int R, bool share_cu) {
   // reduction to deal out) of a sketch up to 64 wide is small enough in LDS for two
   // work-groups per CU (8192-wide layer, R = 16: input gradient 39.8 -> 33.5 us)
   if (share_cu && R <= 64) sl = 2 * NUM_CUS / tiles_m;
+  // No work-group walks more than 24 output tiles: with many tokens and a wide output every
+  // CU otherwise streams its own 64 rows end to end, 16384 rows are being written at once
+  // and the stores crawl ([65536 x 8192 -> 8192], R = 128: forward 1030 us with one run of
+  // 64 tiles per token tile, 550 us with four runs of 16)
+  if (sl < (n_tiles + 23) / 24) sl = (n_tiles + 23) / 24;
   if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
