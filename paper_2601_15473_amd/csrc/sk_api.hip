@@ -12,7 +12,6 @@ namespace {
 
 using namespace sk;
 
-constexpr int NUM_CUS = 256;
 constexpr size_t WS_ALIGN = 256;
 
 thread_local std::string g_hip_error;

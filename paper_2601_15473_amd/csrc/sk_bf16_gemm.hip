@@ -27,27 +27,48 @@ struct GemmTile {
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   static constexpr int STAGE = TA::ELEMS + TB::ELEMS;
   static constexpr int LDS_BYTES = 2 * STAGE * 2;
-  static __device__ __forceinline__ void run(const GemmArgs& p, int block, unsigned char* smem);
+  // stride > 0: the work-group goes on to tiles block + stride, block + 2 stride, ... below
+  // `total` (large tiles only), fetching the next tile's first chunk behind the last
+  // MFMAs of the current one.
+  static __device__ __forceinline__ void run(const GemmArgs& p, int block, unsigned char* smem,
+                                             int stride = 0, int total = 0);
 };
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
           bool COLSUM, int PF>
 __device__ __forceinline__ void
-GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const GemmArgs& p, const int block,
-                                                                      unsigned char* const smem) {
+GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const GemmArgs& p, int block,
+                                                                      unsigned char* const smem,
+                                                                      const int stride, const int total) {
   bf16* const lds = reinterpret_cast<bf16*>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   const int tiles = p.tiles_m * p.tiles_n;
-  const int id = xcd_remap(block, tiles * p.splits);
-  const int split = id / tiles;
-  int tile_m, tile_n;
-  tile_coords(id - split * tiles, p.tiles_m, p.tiles_n, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int k_begin = split * p.k_per_split;
-  const int k_end = (k_begin + p.k_per_split < p.K) ? k_begin + p.k_per_split : p.K;
+  // where work-group index `blk` of the launch works
+  struct Where {
+    int split, tile_m, m0, n0, k_begin, k_end;
+  };
+  auto locate = [&](int blk) {
+    Where w;
+    const int id = xcd_remap(blk, tiles * p.splits);
+    w.split = id / tiles;
+    int tile_n;
+    tile_coords(id - w.split * tiles, p.tiles_m, p.tiles_n, w.tile_m, tile_n);
+    w.m0 = w.tile_m * BM;
+    w.n0 = tile_n * BN;
+    w.k_begin = w.split * p.k_per_split;
+    w.k_end = (w.k_begin + p.k_per_split < p.K) ? w.k_begin + p.k_per_split : p.K;
+    return w;
+  };
+  Where here = locate(block);
+  int chunk = 0;  // chunks done by this work-group: its parity picks the LDS buffer
+  for (bool first_tile = true;; first_tile = false) {
+  const bool has_next = PF == 1 && stride > 0 && block + stride < total;
+  const Where next = has_next ? locate(block + stride) : here;
+  const int split = here.split, tile_m = here.tile_m, m0 = here.m0, n0 = here.n0;
+  const int k_begin = here.k_begin, k_end = here.k_end;
   const int nk = (k_end - k_begin + BK - 1) / BK;
 
   const bf16* __restrict__ A = static_cast<const bf16*>(p.A);
@@ -130,22 +151,29 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
   // Chunks past the end of the k range load as zeros: no branch around any load.
   if (PF == 1) {
     uint4 ra[TA::PIECES], rb[TB::PIECES];
-    TA::load(ra, A, p.lda, m0, p.M, k_begin, k_end, p.K, tid);
-    TB::load(rb, B, p.ldb, n0, p.N, k_begin, k_end, p.K, tid);
-    TA::store(lds, ra, tid);
-    TB::store(lds + TA::ELEMS, rb, tid);
-    __syncthreads();
-    for (int kc = 0; kc < nk; ++kc) {
-      const bf16* As = lds + (kc & 1) * STAGE;
-      bf16* An = lds + ((kc + 1) & 1) * STAGE;
-      const int k0 = k_begin + (kc + 1) * BK;
+    if (first_tile) {
+      TA::load(ra, A, p.lda, m0, p.M, k_begin, k_end, p.K, tid);
+      TB::load(rb, B, p.ldb, n0, p.N, k_begin, k_end, p.K, tid);
+      TA::store(lds, ra, tid);
+      TB::store(lds + TA::ELEMS, rb, tid);
+      __syncthreads();
+    }
+    for (int kc = 0; kc < nk; ++kc, ++chunk) {
+      const bf16* As = lds + (chunk & 1) * STAGE;
+      bf16* An = lds + ((chunk + 1) & 1) * STAGE;
+      // the chunk fetched during this one: the next of this tile, or, behind the last
+      // one, the first of the work-group's next tile
+      const bool into_next = has_next && kc + 1 == nk;
+      const int lm0 = into_next ? next.m0 : m0, ln0 = into_next ? next.n0 : n0;
+      const int k0 = into_next ? next.k_begin : k_begin + (kc + 1) * BK;
+      const int lk_end = into_next ? next.k_end : k_end;
       read(As, 0, fa0, fb0);
       __builtin_amdgcn_sched_barrier(0);
       // k step 0: MFMAs + fragment reads of step 1 + all loads of the next chunk (issued
       // as early as possible: they are stored to LDS three k steps later)
       read(As, 1, fa1, fb1);
-      TA::load(ra, A, p.lda, m0, p.M, k0, k_end, p.K, tid);
-      TB::load(rb, B, p.ldb, n0, p.N, k0, k_end, p.K, tid);
+      TA::load(ra, A, p.lda, lm0, p.M, k0, lk_end, p.K, tid);
+      TB::load(rb, B, p.ldb, ln0, p.N, k0, lk_end, p.K, tid);
       mma(fa0, fb0);
       sched_phase<NMMA, NDSR, NVM, 0>();
       // k step 1
@@ -286,6 +314,22 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
     }
   }
 
+  if (!has_next) break;
+  block += stride;
+  here = next;
+  }  // tiles of this work-group
+}
+
+// The large tiles as a fixed crew of work-groups, one per CU, each walking the tiles
+// index, index + crew, ...: the first chunk of a work-group's next tile is fetched behind
+// the last MFMAs of its current one instead of in a new work-group's prologue.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
+          bool COLSUM, int PF>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_crew_kernel(const GemmArgs p,
+                                                                                 const int total) {
+  typedef GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF> G;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[G::LDS_BYTES];
+  G::run(p, blockIdx.x, smem, gridDim.x, total);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT,
@@ -362,6 +406,12 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   // big per-wave tiles have no registers to spare for a second set of loads in flight
   constexpr int PF = (BM * BN / (WAVES_M * WAVES_N) >= 128 * 64) ? 1 : 2;
+  if constexpr (PF == 1 && !COLSUM && WAVES_M * WAVES_N == 8) if (grid > NUM_CUS) {
+    // more tiles than CUs: one work-group per CU (the tile's LDS admits no second) walks them
+    hipLaunchKernelGGL((gemm_bf16_crew_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>),
+                       dim3((unsigned)NUM_CUS), dim3(64 * WAVES_M * WAVES_N), 0, s, a, (int)grid);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>),
                      dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), 0, s, a);
   return hipGetLastError();

@@ -5,6 +5,8 @@
 
 namespace sk {
 
+constexpr int NUM_CUS = 256;  // compute units of an MI355X
+
 typedef __bf16 bf16;
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
