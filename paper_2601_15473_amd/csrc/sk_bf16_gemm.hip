@@ -406,7 +406,7 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   // big per-wave tiles have no registers to spare for a second set of loads in flight
   constexpr int PF = (BM * BN / (WAVES_M * WAVES_N) >= 128 * 64) ? 1 : 2;
-  if constexpr (PF == 1 && !COLSUM && WAVES_M * WAVES_N == 8) if (grid > NUM_CUS) {
+  if constexpr (PF == 1 && !COLSUM && WAVES_M * WAVES_N == 8) if (grid > NUM_CUS && grid < 0x7fffffffLL - NUM_CUS) {
     // more tiles than CUs: one work-group per CU (the tile's LDS admits no second) walks them
     hipLaunchKernelGGL((gemm_bf16_crew_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>),
                        dim3((unsigned)NUM_CUS), dim3(64 * WAVES_M * WAVES_N), 0, s, a, (int)grid);
