@@ -299,6 +299,29 @@ def test_tall_token_tiles_by_themselves(sk):
     check_all(sk, w, 0)
 
 
+EXTREME_CASES = [
+    (70, 65536, 16, 1, 16), (70, 16, 65536, 1, 16), (33000, 16, 16, 1, 16), (10, 2048, 2048, 8, 256),
+    (1, 16, 16, 1, 16), (4097, 48, 33040, 3, 16), (129, 30000, 272, 1, 272), (65, 4112, 4112, 2, 1024),
+]
+
+
+@pytest.mark.parametrize("shape", EXTREME_CASES, ids=lambda c: "T%d_%dx%d_l%dk%d" % c)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_extreme_aspect_ratios(sk, shape, dtype):
+    """Shapes at the far ends of what the planner sees: one token, 65536-wide sides against
+    16-wide ones, a sketch as wide as the layer, a contraction 30000 long."""
+    T, d_in, d_out, l, k = shape
+    w = W.Workload("extreme", T, d_in, d_out, l, k, dtype, seed=500 + EXTREME_CASES.index(shape))
+    check_all(sk, w, 0)
+    t = W.generate(w)
+    dev = DeviceLayer(t, sk)
+    sk.check(dev.bwd())
+    torch.cuda.synchronize()
+    want = oracle_all(t)
+    for n, got in (("dX", dev.dX), ("dU", dev.dU), ("db", dev.db)):
+        assert rel_err(to_f64(got), want[n]) <= TOL[w.dtype], n
+
+
 def test_bit_reproducible(sk):
     """The token reduction of dU/db runs in a fixed order: two runs agree bit for bit."""
     sk.sk_set_plan(0)
