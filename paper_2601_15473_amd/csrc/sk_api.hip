@@ -73,6 +73,18 @@ int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
   return TILE_64x64;
 }
 
+// fp32 first contraction (one tile shape, 64 x 64): split over a long contraction when its
+// tiles leave most of the chip idle -- ranges at least 256 long, at most 8.
+int f32_first_splits(int64_t M, int64_t N, int64_t K) {
+  const int64_t tiles = ((M + F32_BM - 1) / F32_BM) * ((N + F32_BN - 1) / F32_BN);
+  int64_t sp = NUM_CUS / tiles;
+  if (sp > K / 256) sp = K / 256;
+  if (sp > 8) sp = 8;
+  if (sp < 2 || K < 1024) return 1;
+  const int64_t kps = ((K + sp - 1) / sp + F32_BK - 1) / F32_BK * F32_BK;
+  return (int)((K + kps - 1) / kps);
+}
+
 // A first contraction of the layer run as a general GEMM: bf16 [M, N] result (the narrow
 // intermediate, or its transpose), contraction length K.  Over a long K a small output
 // leaves the choice between small tiles that fill the chip unsplit and large tiles split
@@ -240,6 +252,8 @@ WeightPlan plan_weight(const Shape& s) {
     w.ldz = s.R;
     w.z_bytes = align_up((size_t)s.T * s.R * 4);
     w.z_tile = -1;
+    w.z_splits = f32_first_splits(s.T, s.R, s.in);   // Z = x . S_cat, split like any first GEMM
+    w.zpart_bytes = w.z_splits > 1 ? align_up((size_t)w.z_splits * s.T * s.R * 4) : 0;
   }
   const int64_t splits = t.splits, kps = t.k_per_split;
   w.splits = (int)splits;
@@ -388,6 +402,10 @@ size_t workspace_for(sk_op op, const Shape& s) {
       size_t need = mid;
       if (s.dtype == SK_BF16)   // two GEMMs with the first one split: slabs behind the intermediate
         need += plan_first(s.T, s.R, op == SK_OP_FWD ? s.in : s.out).slab_bytes;
+      else {
+        const int sp = f32_first_splits(s.T, s.R, op == SK_OP_FWD ? s.in : s.out);
+        if (sp > 1) need += align_up((size_t)sp * s.T * s.R * 4);
+      }
       if (s.dtype == SK_BF16 && chain_supported(s.R)) {
         const size_t b = plan_sketch(s, op == SK_OP_FWD ? s.in : s.out).bytes;
         if (b > need) need = b;
@@ -421,7 +439,21 @@ hipError_t gemm(const Shape& s, GemmKind kind, GemmArgs a, hipStream_t st) {
 // contraction into fp32 slabs at `slabs` that are then summed into the bf16 result a.C.
 hipError_t first_gemm(const Shape& s, GemmKind kind, GemmKind kind_slabs, GemmArgs a, void* slabs,
                       hipStream_t st) {
-  if (s.dtype != SK_BF16) return launch_gemm_f32(kind, a, st);
+  if (s.dtype != SK_BF16) {
+    const int splits = f32_first_splits(a.M, a.N, a.K);
+    if (splits == 1) return launch_gemm_f32(kind, a, st);
+    // fp32: the same kernel writes the slabs (one per range of the contraction); summed in order
+    float* out = static_cast<float*>(a.C);
+    a.C = slabs; a.splits = splits;
+    a.k_per_split = (int)(((a.K + splits - 1) / splits + F32_BK - 1) / F32_BK * F32_BK);
+    a.splits = (a.K + a.k_per_split - 1) / a.k_per_split;
+    const hipError_t e = launch_gemm_f32(kind, a, st);
+    if (e != hipSuccess) return e;
+    ReduceArgs r{};
+    r.part = static_cast<const float*>(slabs); r.out = out; r.n = (int64_t)a.M * a.N; r.scale = 1.0f;
+    r.splits = a.splits; r.splits2 = 1; r.scale2 = 1.0f;
+    return launch_reduce_splits(r, st);
+  }
   const FirstPlan f = plan_first(a.M, a.N, a.K);
   if (f.splits == 1) return launch_gemm_bf16(kind, f.tile, a, st);
   void* out = a.C;
@@ -606,7 +638,8 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
     }
     a.A = Z; a.lda = w.ldz;
   } else {
-    e = launch_gemm_f32(GEMM_NN, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr), hs);
+    e = first_gemm(s, GEMM_NN, GEMM_NN_F32, dense_args(x, in, S_cat, s.R, Z, s.R, tokens, s.R, in, 1.0f, nullptr),
+                   ws + w.z_bytes + w.part_bytes + w.csum_bytes, hs);
     a.A = Z; a.lda = s.R;
   }
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (x.S)");

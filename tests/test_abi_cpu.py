@@ -66,7 +66,8 @@ def test_workspace_query_and_check():
             mid = 1000 * 128 * e
             for op in (sk.SK_OP_FWD, sk.SK_OP_BWD_INPUT):
                 ws = sk.sk_linear_workspace_bytes(op, *a)
-                assert ws >= mid and ws % 256 == 0 and ws <= 8 * 4 * 1000 * 128 + 256
+                # the intermediate, plus at most eight fp32 slabs of a split first contraction
+                assert ws >= mid and ws % 256 == 0 and ws <= mid + 8 * 4 * 1000 * 128 + 512
             assert sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT, *a) >= mid
         need = sk.sk_linear_workspace_bytes(sk.SK_OP_FWD, *ARGS)
         assert sk.sk_linear_fwd(P, P, P, P, P, *ARGS, P, need - 1) == sk.SK_ERR_WORKSPACE
