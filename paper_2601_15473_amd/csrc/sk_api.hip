@@ -145,6 +145,9 @@ struct WeightPlan {
   bool own_colsum;     // db from its own kernel (the big tile has no registers for it)
   int colsum_splits;   // rows of column-sum partials: `splits`, or the own kernel's row runs
   int colsum_rows;     // tokens per row run of the own kernel
+  // Uneven split (big tile only): the first head_cols output columns are one full round
+  // of tiles over all tokens, straight into dU; only the rest is split over the tokens.
+  int head_cols;       // 0: the whole output is split evenly (`splits`)
   int z_tile;          // bf16: tile of the GEMM that recomputes Z^T
   int z_splits;        // split of that GEMM over `in` (fp32 slabs, summed into bf16 Z^T)
   int z_k_per_split;
@@ -273,7 +276,30 @@ WeightPlan plan_weight(const Shape& s) {
     w.colsum_rows = (int)rows;
     w.colsum_splits = (int)((s.T + rows - 1) / rows);
   }
-  w.part_bytes = splits > 1 ? align_up((size_t)splits * s.R * s.out * 4) : 0;
+  w.head_cols = 0;
+  if (w.own_colsum && splits > 1 && s.R <= 65535 && !getenv("SK_TUNE_WSPLITS")) {
+    // More tiles than CUs but fewer than two rounds (c4: 344 tiles of 256 x 256): a round of
+    // whole-token tiles covering as many tile columns as fit, then the remaining columns
+    // split over the tokens so that they fill one more, shorter round.  Against the even
+    // split that is the same MFMA time with a fraction of the slabs (c4: 2 x 90 MB -> 2 x 23 MB).
+    const int64_t tm = (s.R + 255) / 256, tn = (s.out + 255) / 256;
+    const int64_t head_tn = NUM_CUS / tm;
+    if (tm * tn > NUM_CUS && tm * tn < 2 * NUM_CUS && head_tn >= 1 && head_tn < tn &&
+        head_tn * tm * 4 >= NUM_CUS * 3) {
+      const int64_t tail_tiles = (tn - head_tn) * tm;
+      int64_t sp = NUM_CUS / tail_tiles;
+      if (sp > (s.T + 1023) / 1024) sp = (s.T + 1023) / 1024;
+      if (sp > 8) sp = 8;
+      if (sp >= 2) {
+        int64_t k2 = ((s.T + sp - 1) / sp + 63) / 64 * 64;
+        w.head_cols = (int)(head_tn * 256);
+        w.splits = (int)((s.T + k2 - 1) / k2);
+        w.k_per_split = (int)k2;
+      }
+    }
+  }
+  const int64_t split_cols = s.out - w.head_cols;
+  w.part_bytes = w.splits > 1 ? align_up((size_t)w.splits * s.R * split_cols * 4) : 0;
   w.csum_bytes = w.colsum_splits > 1 ? align_up((size_t)w.colsum_splits * s.out * 4) : 0;
   return w;
 }
@@ -660,13 +686,29 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
                              w.colsum_splits, w.colsum_rows, hs);
       if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (column sums)");
     }
+    if (w.head_cols > 0) {
+      // first round: whole-token tiles of the first head_cols columns, straight into dU
+      GemmArgs hd = a;
+      hd.N = w.head_cols; hd.C = dU_cat; hd.colsum = nullptr; hd.scale = scale;
+      hd.splits = 1; hd.k_per_split = (int)((tokens + 63) / 64 * 64);
+      e = launch_gemm_bf16(GEMM_NN_F32, w.tile, hd, hs);
+      if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (Z^T.dY, first columns)");
+      // second, shorter round: the remaining columns, split over the tokens into slabs
+      a.B = static_cast<const unsigned char*>(dY) + (size_t)w.head_cols * s.esize;
+      a.N = (int)out - w.head_cols; a.ldc = a.N; a.C = part; a.colsum = nullptr; a.scale = 1.0f;
+    }
     e = launch_gemm_bf16(GEMM_NN_F32, w.tile, a, hs);
   } else {
     e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs)
                            : launch_gemm_f32(GEMM_TN_F32, a, hs);
   }
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (Z^T.dY)");
-  const bool sum_dU = w.splits > 1;
+  if (w.head_cols > 0) {
+    e = launch_reduce_splits_2d(part, dU_cat + w.head_cols, s.R, (int)out - w.head_cols, out, w.splits,
+                                scale, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (sum of the split columns)");
+  }
+  const bool sum_dU = w.splits > 1 && w.head_cols == 0;
   const bool sum_db = dbias && w.colsum_splits > 1;
   if (sum_dU || sum_db) {
     ReduceArgs r{};

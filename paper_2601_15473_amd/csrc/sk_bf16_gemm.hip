@@ -557,6 +557,32 @@ hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, in
   return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void reduce_splits_2d_kernel(const float* __restrict__ part,
+                                                               float* __restrict__ out, int rows, int cols,
+                                                               int64_t ld_out, int splits, float scale) {
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  const int r = blockIdx.y;
+  if (c >= cols) return;
+  const int64_t n = (int64_t)rows * cols, at = (int64_t)r * cols + c;
+  float4 s = *reinterpret_cast<const float4*>(part + at);
+#pragma unroll 8
+  for (int k = 1; k < splits; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + at);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  *reinterpret_cast<float4*>(out + (int64_t)r * ld_out + c) =
+      make_float4(s.x * scale, s.y * scale, s.z * scale, s.w * scale);
+}
+
+hipError_t launch_reduce_splits_2d(const float* part, float* out, int rows, int cols, int64_t ld_out,
+                                   int splits, float scale, hipStream_t s) {
+  if (rows < 1 || rows > 65535 || cols < 4 || (cols & 3) != 0 || splits < 1) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)((cols / 4 + 255) / 256), (unsigned)rows);
+  hipLaunchKernelGGL(reduce_splits_2d_kernel, grid, dim3(256), 0, s, part, out, rows, cols, ld_out, splits,
+                     scale);
+  return hipGetLastError();
+}
+
 hipError_t launch_reduce_to_bf16(const float* part, void* out, int64_t n, int splits, hipStream_t s) {
   if (n <= 0 || (n & 3) != 0 || splits < 1) return hipErrorInvalidValue;
   const int64_t groups = (n / 4 + 255) / 256;

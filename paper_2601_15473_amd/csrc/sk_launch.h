@@ -45,6 +45,10 @@ hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s);
 // out[i] = bf16(sum over s of part[s][i]), i < n (n a multiple of 4; slabs n elements apart,
 // summed in index order)
 hipError_t launch_reduce_to_bf16(const float* part, void* out, int64_t n, int splits, hipStream_t s);
+// out[r * ld_out + c] = scale * sum over s of part[s][r * cols + c] (r < rows, c < cols, cols a multiple of 4;
+// slabs rows * cols elements apart, summed in index order): a column range of a wider matrix
+hipError_t launch_reduce_splits_2d(const float* part, float* out, int rows, int cols, int64_t ld_out,
+                                   int splits, float scale, hipStream_t s);
 // Two GEMMs that do not depend on each other in one launch (see dual_gemm_kernel); built
 // for a few (kind, tile) pairs only -- ask dual_gemm_supported first.  `a` should be the
 // longer-running one.
