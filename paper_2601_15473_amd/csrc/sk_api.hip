@@ -681,7 +681,10 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
     a.C = part; a.colsum = dbias ? cpart : nullptr; a.scale = 1.0f;
   }
   if (s.dtype == SK_BF16 && w.own_colsum) {
-    if (dbias) {
+    // the bias gradient from its own kernel -- or, with the uneven split, inside the launch of
+    // the second, shorter round, whose GEMM leaves CUs free
+    const bool ride = dbias && w.head_cols > 0 && w.tile == TILE_256x256_W8;
+    if (dbias && !ride) {
       e = launch_colsum_bf16(dY, w.colsum_splits == 1 ? dbias : cpart, (int)tokens, (int)out,
                              w.colsum_splits, w.colsum_rows, hs);
       if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (column sums)");
@@ -697,7 +700,11 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
       a.B = static_cast<const unsigned char*>(dY) + (size_t)w.head_cols * s.esize;
       a.N = (int)out - w.head_cols; a.ldc = a.N; a.C = part; a.colsum = nullptr; a.scale = 1.0f;
     }
-    e = launch_gemm_bf16(GEMM_NN_F32, w.tile, a, hs);
+    if (ride)
+      e = launch_gemm_f32slabs_with_colsum(w.tile, a, dY, w.colsum_splits == 1 ? dbias : cpart, (int)tokens,
+                                           (int)out, w.colsum_splits, w.colsum_rows, hs);
+    else
+      e = launch_gemm_bf16(GEMM_NN_F32, w.tile, a, hs);
   } else {
     e = s.dtype == SK_BF16 ? launch_gemm_bf16(GEMM_NN_F32_COLSUM, w.tile, a, hs)
                            : launch_gemm_f32(GEMM_TN_F32, a, hs);

@@ -455,18 +455,21 @@ hipError_t launch_gemm_bf16(GemmKind kind, int tile, const GemmArgs& a, hipStrea
 // per instruction (lane = 8 columns), the four waves stride over the rows, and their
 // four partial sums meet in LDS and are added in wave order.
 constexpr int COLSUM_COLS = 512;
-__global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* __restrict__ in,
-                                                          float* __restrict__ out, int rows,
-                                                          int cols, int rows_per_split) {
-  __shared__ float part[4][COLSUM_COLS + 8];
+// The work of one work-group of NW waves at grid position (bx, by); `part` is NW rows of
+// COLSUM_COLS + 8 floats of LDS.
+template <int NW>
+__device__ __forceinline__ void colsum_body(const unsigned short* __restrict__ in, float* __restrict__ out,
+                                            int rows, int cols, int rows_per_split, int bx, int by,
+                                            float* part) {
+  constexpr int PLD = COLSUM_COLS + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = blockIdx.x * COLSUM_COLS + lane * 8;
-  const int r_begin = blockIdx.y * rows_per_split;
+  const int c = bx * COLSUM_COLS + lane * 8;
+  const int r_begin = by * rows_per_split;
   const int r_end = (r_begin + rows_per_split < rows) ? r_begin + rows_per_split : rows;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (c < cols) {
 #pragma unroll 8
-    for (int r = r_begin + wave; r < r_end; r += 4) {
+    for (int r = r_begin + wave; r < r_end; r += NW) {
       const uint4 v = *reinterpret_cast<const uint4*>(in + (int64_t)r * cols + c);
       const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -477,12 +480,42 @@ __global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* 
     }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) part[wave][lane * 8 + e] = acc[e];
+  for (int e = 0; e < 8; ++e) part[wave * PLD + lane * 8 + e] = acc[e];
   __syncthreads();
-  for (int i = tid; i < COLSUM_COLS; i += 256) {
-    const int gc = blockIdx.x * COLSUM_COLS + i;
-    if (gc < cols)
-      out[(int64_t)blockIdx.y * cols + gc] = ((part[0][i] + part[1][i]) + part[2][i]) + part[3][i];
+  for (int i = tid; i < COLSUM_COLS; i += 64 * NW) {
+    const int gc = bx * COLSUM_COLS + i;
+    if (gc < cols) {
+      float s = part[i];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) s += part[w * PLD + i];   // in wave order
+      out[(int64_t)by * cols + gc] = s;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void colsum_bf16_kernel(const unsigned short* __restrict__ in,
+                                                          float* __restrict__ out, int rows,
+                                                          int cols, int rows_per_split) {
+  __shared__ float part[4 * (COLSUM_COLS + 8)];
+  colsum_body<4>(in, out, rows, cols, rows_per_split, blockIdx.x, blockIdx.y, part);
+}
+
+// An eight-wave GEMM launch that does not fill the chip, with the column sums riding
+// along: work-groups past the GEMM's own run the column-sum body (eight waves each) on
+// the CUs the GEMM leaves free -- one streams from HBM while the other multiplies.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT, int PF>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_with_colsum_kernel(
+    const GemmArgs p, const int gemm_groups, const ColsumArgs c) {
+  typedef GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, false, PF> G;
+  static_assert(G::NTH == 512, "the column-sum body here runs eight waves");
+  static_assert(G::LDS_BYTES >= 8 * (COLSUM_COLS + 8) * 4, "LDS of the GEMM tile covers the partial sums");
+  __shared__ __attribute__((aligned(16))) unsigned char smem[G::LDS_BYTES];
+  if ((int)blockIdx.x < gemm_groups) {
+    G::run(p, blockIdx.x, smem);
+  } else {
+    const int w = blockIdx.x - gemm_groups;
+    colsum_body<8>(static_cast<const unsigned short*>(c.in), c.out, c.rows, c.cols, c.rows_per_split,
+                   w % c.col_groups, w / c.col_groups, reinterpret_cast<float*>(smem));
   }
 }
 
@@ -546,6 +579,22 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
     case 6: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x64, NT_128x64>), grid, block, 0, s, a, b, (int)ga); break;
     default: return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_f32slabs_with_colsum(int tile, GemmArgs a, const void* in, float* out, int rows,
+                                            int cols, int splits, int rows_per_split, hipStream_t s) {
+  if (tile != TILE_256x256_W8) return hipErrorInvalidValue;
+  a.tiles_m = (a.M + 255) / 256;
+  a.tiles_n = (a.N + 255) / 256;
+  ColsumArgs c;
+  c.in = in; c.out = out; c.rows = rows; c.cols = cols; c.rows_per_split = rows_per_split;
+  c.col_groups = (cols + COLSUM_COLS - 1) / COLSUM_COLS;
+  const long long gg = (long long)a.tiles_m * a.tiles_n * a.splits;
+  const long long grid = gg + (long long)c.col_groups * splits;
+  if (gg <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>),
+                     dim3((unsigned)grid), dim3(512), 0, s, a, (int)gg, c);
   return hipGetLastError();
 }
 

@@ -40,6 +40,14 @@ struct GemmArgs {
   float scale;
 };
 
+// Column sums of a dense row-major bf16 matrix [rows, cols]: out[run][c] = sum of the rows
+// of run `run` (rows_per_split rows each), for col_groups groups of 512 columns.
+struct ColsumArgs {
+  const void* in;
+  float* out;
+  int rows, cols, rows_per_split, col_groups;
+};
+
 // Sum of split-K slabs in split order (deterministic), two outputs in one launch:
 //   out[i]  = scale  * sum_s part[s][i]   for i < n      (slabs n elements apart)
 //   out2[j] = scale2 * sum_s part2[s][j]  for j < n2     (splits2 slabs n2 elements apart; n2 may be 0)

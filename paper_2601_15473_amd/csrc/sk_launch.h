@@ -59,6 +59,10 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
 // `cols` sums per run of rows_per_split rows (splits runs)
 hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,
                               int rows_per_split, hipStream_t s);
+// The split-K GEMM_NN_F32 `a` on the eight-wave 256 x 256 tile with the column sums above
+// computed in the same launch, on the CUs the GEMM's work-groups leave free.
+hipError_t launch_gemm_f32slabs_with_colsum(int tile, GemmArgs a, const void* in, float* out, int rows,
+                                            int cols, int splits, int rows_per_split, hipStream_t s);
 
 // Second contraction of the layer with the R-wide intermediate of a 64-token tile
 // resident on chip (bf16, R <= 512), optionally with the first contraction fused in:
