@@ -415,8 +415,17 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
 // storage type, then the token-split slabs of dA [in, nc].
 size_t first_stage_bytes(const Shape& s, int64_t nc) {
   const TokenPlan t = plan_tokens(s.in, nc, s.T, s.dtype, false);
-  return align_up((size_t)s.T * nc * s.esize) +
-         (t.splits > 1 ? align_up((size_t)t.splits * s.in * nc * 4) : 0);
+  const size_t da_slabs = t.splits > 1 ? align_up((size_t)t.splits * s.in * nc * 4) : 0;
+  // slabs of G when its GEMM is split over `out`: dead once summed, so they share the
+  // region of the dA slabs
+  size_t g_slabs;
+  if (s.dtype == SK_BF16) {
+    g_slabs = plan_first(s.T, nc, s.out).slab_bytes;
+  } else {
+    const int sp = f32_first_splits(s.T, nc, s.out);
+    g_slabs = sp > 1 ? align_up((size_t)sp * s.T * nc * 4) : 0;
+  }
+  return align_up((size_t)s.T * nc * s.esize) + (da_slabs > g_slabs ? da_slabs : g_slabs);
 }
 
 size_t workspace_for(sk_op op, const Shape& s) {
@@ -856,7 +865,8 @@ sk_status sk_linear_bwd_weight_first(const void* x, const void* U_cat, const voi
   const unsigned char* U_sub = static_cast<const unsigned char*>(U_cat) + (size_t)col_begin * out * s.esize;
 
   // G = dY . U_sub^T, rounded to the storage type like the input gradient's intermediate
-  hipError_t e = gemm(s, GEMM_NT, dense_args(dY, out, U_sub, out, G, nc, tokens, nc, out, 1.0f, nullptr), hs);
+  hipError_t e = first_gemm(s, GEMM_NT, GEMM_NT_F32,
+                            dense_args(dY, out, U_sub, out, G, nc, tokens, nc, out, 1.0f, nullptr), part, hs);
   if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight_first (dY.U^T)");
 
   // dA = scale * x^T . G, the token axis split in order
