@@ -18,6 +18,12 @@ CASES = [
     W.Workload("two_bf16_bert_base", 1000, 768, 3072, 1, 64, "bf16", seed=23),   # R' = 128 like c1
     W.Workload("two_bf16_square", 700, 768, 768, 2, 64, "bf16", seed=24),
     W.Workload("two_bf16_wide", 600, 1024, 4096, 2, 128, "bf16", seed=25),       # R' = 512 like c3
+    # the benchmark's own shape: the first GEMM of the first-stage gradient (64 tiles over a
+    # contraction 3072 long) runs split into fp32 slabs
+    W.Workload("two_bf16_bert_base_full", 4096, 768, 3072, 1, 64, "bf16", seed=27),
+    # long ragged contractions on both sides, ragged token tile
+    W.Workload("two_bf16_long_ragged", 520, 4112, 2064, 1, 48, "bf16", seed=28),
+    W.Workload("two_f32_long_ragged", 200, 1040, 2064, 1, 16, "f32", seed=29),
 ]
 
 
