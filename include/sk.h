@@ -105,6 +105,30 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
                                size_t workspace_bytes, void* stream);
 
 /*
+ * sk_linear_bwd_weight for callers that cannot allocate or supply a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs, kernels and results (bit for bit) as sk_linear_bwd_weight, with the workspace
+ * (the recomputed x . S_cat, the token-split slabs, the column-sum partials) in a fixed
+ * array of SK_NOALLOC_SCRATCH_BYTES = 32 MiB of device memory that is part of the loaded
+ * library: every GPU the library runs on holds one copy until the process ends.  The call
+ * makes no hipMalloc / hipFree and no allocating library call; it looks the array's address
+ * up once per device (hipGetSymbolAddress) on the first call there.
+ *   - Shapes whose sk_linear_workspace_bytes(SK_OP_BWD_WEIGHT, ...) exceeds that size return
+ *     SK_ERR_WORKSPACE with nothing enqueued (BERT-base and BERT-large layer sizes fit; a
+ *     2048-wide sketch over 16384 tokens does not).
+ *   - All calls on one GPU share the array: two calls that can overlap there (different
+ *     streams, or two threads) race on it; serialise them.  Its contents after a call are
+ *     undefined; nothing has to be cleared between calls.
+ *   - The GPU used is the calling thread's current device, which must be the one `stream`
+ *     and the pointers belong to.
+ */
+#define SK_NOALLOC_SCRATCH_BYTES (32u << 20)
+sk_status sk_linear_bwd_weight_noalloc(const void* x, const void* S_cat, const void* dY,
+                                       float* dU_cat, float* dbias, int64_t tokens, int64_t in,
+                                       int64_t out, int32_t l, int32_t k, sk_dtype dtype,
+                                       void* stream);
+
+/*
  * Both gradients in one call: what sk_linear_bwd_input followed by sk_linear_bwd_weight
  * compute (same formulas, same outputs, same rounding points; the order of the fp32
  * partial sums inside dX may differ from the separate call's, dU_cat and dbias are

@@ -8,6 +8,13 @@
 #include "../../include/sk.h"
 #include "sk_launch.h"
 
+// Scratch of sk_linear_bwd_weight_noalloc (SK_NOALLOC_SCRATCH_BYTES, include/sk.h): device
+// memory that belongs to the loaded code object (one copy per GPU, held until the process
+// ends), so that entry point needs no workspace from its caller and no allocation of its
+// own.  In host code this name is only a handle for hipGetSymbolAddress; kernels are given
+// the address that call returns.
+static __device__ __align__(256) unsigned char scratch[SK_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace sk;
@@ -735,6 +742,40 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
     if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight (sum of splits)");
   }
   return SK_OK;
+}
+
+sk_status sk_linear_bwd_weight_noalloc(const void* x, const void* S_cat, const void* dY,
+                                       float* dU_cat, float* dbias, int64_t tokens, int64_t in,
+                                       int64_t out, int32_t l, int32_t k, sk_dtype dtype,
+                                       void* stream) {
+  // everything sk_linear_bwd_weight would reject is rejected here first, before any HIP call
+  if (!x || !S_cat || !dY || !dU_cat) return SK_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(S_cat) || !aligned16(dY) || !aligned16(dU_cat) || !aligned16(dbias))
+    return SK_ERR_INVALID_ARG;
+  Shape s;
+  const sk_status st = check_shape(tokens, in, out, l, k, dtype, s);
+  if (st != SK_OK) return st;
+  if (workspace_for(SK_OP_BWD_WEIGHT, s) > SK_NOALLOC_SCRATCH_BYTES) return SK_ERR_WORKSPACE;
+  // the address of this GPU's copy of the array, looked up once per device
+  constexpr int MAX_DEVICES = 64;
+  static std::atomic<void*> device_scratch[MAX_DEVICES];
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd_weight_noalloc (hipGetDevice)");
+  if (dev < 0 || dev >= MAX_DEVICES) return SK_ERR_UNSUPPORTED;
+  void* ptr = device_scratch[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr)
+      return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol,
+                      "sk_linear_bwd_weight_noalloc (hipGetSymbolAddress)");
+    device_scratch[dev].store(ptr, std::memory_order_release);
+  }
+  // Every region of the workspace is written by the call before it is read (Z^T with its
+  // zero-filled row padding, the split slabs, the column-sum partials), so what an earlier
+  // call left in the array needs no clearing.
+  return sk_linear_bwd_weight(x, S_cat, dY, dU_cat, dbias, tokens, in, out, l, k, dtype, ptr,
+                              SK_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const void* U_cat,

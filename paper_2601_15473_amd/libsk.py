@@ -27,6 +27,7 @@ LIB_PATH = os.path.join(_HERE, "lib", "libsk.so")
 
 SK_OK, SK_ERR_INVALID_ARG, SK_ERR_UNSUPPORTED, SK_ERR_WORKSPACE, SK_ERR_HIP = range(5)
 SK_F32, SK_BF16 = 0, 1
+SK_NOALLOC_SCRATCH_BYTES = 32 << 20   # fixed scratch of sk_linear_bwd_weight_noalloc
 SK_OP_FWD, SK_OP_BWD_INPUT, SK_OP_BWD_WEIGHT, SK_OP_BWD_WEIGHT_FIRST, SK_OP_BWD = 0, 1, 2, 3, 4
 DTYPES = {"f32": SK_F32, "bf16": SK_BF16}
 
@@ -46,6 +47,9 @@ _lib.sk_linear_bwd_input.restype = ctypes.c_int
 _lib.sk_linear_bwd_input.argtypes = [_vp, _vp, _vp, _vp] + _tail
 _lib.sk_linear_bwd_weight.restype = ctypes.c_int
 _lib.sk_linear_bwd_weight.argtypes = [_vp, _vp, _vp, _vp, _vp] + _tail
+_lib.sk_linear_bwd_weight_noalloc.restype = ctypes.c_int
+_lib.sk_linear_bwd_weight_noalloc.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i32, _i32,
+                                              ctypes.c_int, _vp]
 _lib.sk_linear_bwd.restype = ctypes.c_int
 _lib.sk_linear_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp] + _tail
 _lib.sk_linear_bwd_weight_first.restype = ctypes.c_int
@@ -61,7 +65,7 @@ _lib.sk_set_plan.restype = ctypes.c_int
 _lib.sk_set_plan.argtypes = [ctypes.c_int]
 
 EXPORTS = ("sk_linear_fwd", "sk_linear_bwd_input", "sk_linear_bwd_weight", "sk_linear_bwd",
-           "sk_linear_bwd_weight_first",
+           "sk_linear_bwd_weight_first", "sk_linear_bwd_weight_noalloc",
            "sk_linear_workspace_bytes", "sk_status_string", "sk_last_hip_error", "sk_set_plan")
 
 
@@ -107,6 +111,12 @@ def sk_linear_bwd_weight(x, S_cat, dY, dU_cat, dbias, tokens, d_in, d_out, l, k,
     return _lib.sk_linear_bwd_weight(_ptr(x), _ptr(S_cat), _ptr(dY), _ptr(dU_cat), _ptr(dbias),
                                      tokens, d_in, d_out, l, k, dtype,
                                      _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def sk_linear_bwd_weight_noalloc(x, S_cat, dY, dU_cat, dbias, tokens, d_in, d_out, l, k, dtype,
+                                 stream=None):
+    return _lib.sk_linear_bwd_weight_noalloc(_ptr(x), _ptr(S_cat), _ptr(dY), _ptr(dU_cat), _ptr(dbias),
+                                             tokens, d_in, d_out, l, k, dtype, _stream(stream))
 
 
 def sk_linear_bwd(x, dY, S_cat, U_cat, dX, dU_cat, dbias, tokens, d_in, d_out, l, k, dtype,

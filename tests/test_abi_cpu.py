@@ -121,3 +121,17 @@ def test_single_call_backward_argument_checks_and_workspace():
                  sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT, *a))
         assert both == parts            # the two gradients' buffers side by side
         assert f(P, P, P, P, P, P, None, *a, P, both - 1) == sk.SK_ERR_WORKSPACE
+
+
+def test_noalloc_entry_rejects_before_any_hip_call():
+    f = sk.sk_linear_bwd_weight_noalloc
+    assert f(None, P, P, P, P, *ARGS) == sk.SK_ERR_INVALID_ARG
+    assert f(P, P, P, P, P + 4, *ARGS) == sk.SK_ERR_INVALID_ARG
+    assert f(P, P, P, P, None, 64, 64, 60, 1, 16, sk.SK_BF16) == sk.SK_ERR_UNSUPPORTED
+    # a workspace larger than the fixed scratch array: refused, nothing enqueued
+    big = (16384, 4096, 11008, 8, 256, sk.SK_BF16)
+    assert sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT, *big) > sk.SK_NOALLOC_SCRATCH_BYTES
+    assert f(P, P, P, P, None, *big) == sk.SK_ERR_WORKSPACE
+    hdr = open(os.path.join(ROOT, "include", "sk.h")).read()
+    assert re.search(r"#define SK_NOALLOC_SCRATCH_BYTES \(32u << 20\)", hdr)
+    assert sk.SK_NOALLOC_SCRATCH_BYTES == 32 << 20
