@@ -14,6 +14,7 @@ There is no CPU path: tensors that are not on a GPU raise.
 """
 from __future__ import annotations
 
+import collections
 import math
 
 import torch
@@ -21,18 +22,30 @@ import torch
 from . import libsk as sk
 
 _DTYPES = {torch.float32: sk.SK_F32, torch.bfloat16: sk.SK_BF16}
-_workspaces: dict = {}
+_workspaces: "collections.OrderedDict" = collections.OrderedDict()
+_MAX_WORKSPACES = 8
 
 
 def _workspace(device: torch.device, stream: int, nbytes: int) -> torch.Tensor:
-    """One scratch buffer per (device, stream): calls on a stream run in order, so they
-    can share it; it only ever grows."""
+    """One scratch buffer per (device, stream): calls on a stream run in order, so they can
+    share it.  A buffer grows to the largest request seen on its stream; at most
+    ``_MAX_WORKSPACES`` streams keep one (least recently used dropped first: torch's caching
+    allocator keeps a dropped buffer alive until the work queued on it is done), and
+    ``release_workspaces()`` drops them all."""
     key = (device.index, stream)
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
         ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
         _workspaces[key] = ws
+    _workspaces.move_to_end(key)
+    while len(_workspaces) > _MAX_WORKSPACES:
+        _workspaces.popitem(last=False)
     return ws
+
+
+def release_workspaces() -> None:
+    """Give the layers' scratch buffers back to the allocator (they are re-created on demand)."""
+    _workspaces.clear()
 
 
 def _check(x: torch.Tensor, name: str, dtype: torch.dtype):
@@ -182,10 +195,12 @@ class SKLinearTwoSidedFunction(torch.autograd.Function):
 
     Arguments: S1_cat [in, l*k] and S2T_cat [l*k, out] fixed, U1_cat [l*k, out] and U2_cat
     [in, l*k] learned.  The layer is the one-sided chain on [S1 | U2] and [U1 ; S2^T] with 2 l
-    terms; the two concatenations are copies made here, everything else runs in libsk."""
+    terms; ``stage`` may carry those two concatenations ready made (the module caches them
+    until a learned factor changes), otherwise they are copied together here; everything else
+    runs in libsk."""
 
     @staticmethod
-    def forward(ctx, x, S1_cat, U1_cat, U2_cat, S2T_cat, bias, l, k):
+    def forward(ctx, x, S1_cat, U1_cat, U2_cat, S2T_cat, bias, l, k, stage=None):
         dtype = S1_cat.dtype
         if dtype not in _DTYPES:
             raise TypeError(f"SKLinear: dtype {dtype} is not supported (float32 or bfloat16)")
@@ -196,8 +211,11 @@ class SKLinearTwoSidedFunction(torch.autograd.Function):
         if half != l * k or U1_cat.shape[0] != half or U2_cat.shape != (d_in, half) or \
                 S2T_cat.shape != (half, d_out) or x.shape[-1] != d_in:
             raise ValueError("SKLinear (two-sided): shapes do not match")
-        A_cat = torch.cat([S1_cat, U2_cat], dim=1).contiguous()
-        B_cat = torch.cat([U1_cat, S2T_cat], dim=0).contiguous()
+        if stage is not None:
+            A_cat, B_cat = stage
+        else:
+            A_cat = torch.cat([S1_cat, U2_cat], dim=1).contiguous()
+            B_cat = torch.cat([U1_cat, S2T_cat], dim=0).contiguous()
         x2 = x.reshape(-1, d_in).contiguous()
         bias_c = bias.contiguous() if bias is not None else None
         tokens = x2.shape[0]
@@ -235,7 +253,7 @@ class SKLinearTwoSidedFunction(torch.autograd.Function):
                                                    half, half, dt, ws, ws.numel(), stream))
         # the rows of dB below `half` belong to S2^T: gradients of fixed numbers, dropped
         return (dX.reshape(ctx.x_shape), None, dB[:half].to(dtype), dA.to(dtype), None,
-                db.to(dtype) if db is not None else None, None, None)
+                db.to(dtype) if db is not None else None, None, None, None)
 
 
 class SKLinearTwoSided(torch.nn.Module):
@@ -266,15 +284,30 @@ class SKLinearTwoSided(torch.nn.Module):
         self.register_buffer("S2T_cat", S2T)
         self.U1_cat = torch.nn.Parameter((S1.float().t() @ W.t()).to(dtype))       # [l*k, out]
         self.U2_cat = torch.nn.Parameter((W.t() @ S2T.float().t()).to(dtype))      # [in, l*k]
+        self._stage, self._stage_key = None, None
         if bias:
             b = (torch.rand(out_features, generator=g) * 2 - 1) * bound
             self.bias = torch.nn.Parameter(b.to(dtype).to(device))
         else:
             self.register_parameter("bias", None)
 
+    def _stage_matrices(self):
+        """[S1 | U2] and [U1 ; S2^T], rebuilt only when a learned factor (or a buffer) has been
+        written since the cached copies were made -- tensors count their in-place writes, which
+        is how optimizers update parameters.  Stale copies are replaced, never overwritten: a
+        backward pass that is still to come holds the ones its forward pass used."""
+        parts = (self.S1_cat, self.U2_cat, self.U1_cat, self.S2T_cat)
+        key = tuple((t.data_ptr(), t._version, t.dtype) for t in parts)
+        if self._stage_key != key:
+            with torch.no_grad():
+                self._stage = (torch.cat([self.S1_cat, self.U2_cat], dim=1).contiguous(),
+                               torch.cat([self.U1_cat, self.S2T_cat], dim=0).contiguous())
+            self._stage_key = key
+        return self._stage
+
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         return SKLinearTwoSidedFunction.apply(x, self.S1_cat, self.U1_cat, self.U2_cat, self.S2T_cat,
-                                              self.bias, self.num_terms, self.low_rank)
+                                              self.bias, self.num_terms, self.low_rank, self._stage_matrices())
 
     def extra_repr(self) -> str:
         return (f"in_features={self.in_features}, out_features={self.out_features}, "

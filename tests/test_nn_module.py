@@ -125,3 +125,33 @@ def test_two_sided_module_matches_its_oracle(dtype, tol):
         e = rel_err(got[n], want[n])
         print(f"   {n}: {e:.2e}", flush=True)
         assert e <= tol, (n, e)
+
+
+@pytest.mark.gpu
+def test_two_sided_module_rebuilds_its_stage_matrices_after_an_update():
+    """The module keeps [S1 | U2] and [U1 ; S2^T] between calls; an in-place update of a learned
+    factor (an optimizer step) must show in the next forward pass, and a second forward pass
+    with unchanged factors must reuse the copies."""
+    from oracle import sklinear_two_sided as O2
+    from paper_2601_15473_amd import nn as sknn
+    from skgpu import rel_err, to_f64
+    l, k, d_in, d_out, T = 1, 16, 64, 48, 40
+    m = sknn.SKLinearTwoSided(d_in, d_out, l, k, bias=True, dtype=torch.float32, seed=5)
+    x = torch.randn(T, d_in, generator=torch.Generator().manual_seed(6)).cuda()
+
+    def oracle():
+        S1c, U1c, U2c, S2Tc = (to_f64(t) for t in (m.S1_cat, m.U1_cat, m.U2_cat, m.S2T_cat))
+        return O2.forward(to_f64(x), S1c[None], U1c[None], U2c[None], S2Tc.T[None], to_f64(m.bias))
+
+    y0 = m(x)
+    first = m._stage
+    assert rel_err(to_f64(y0), oracle()) <= 1e-4
+    m(x)
+    assert m._stage is first                       # nothing changed: no new copies
+    opt = torch.optim.SGD(m.parameters(), lr=0.5)
+    m(x).square().sum().backward()
+    opt.step()
+    y1 = m(x)
+    assert m._stage is not first
+    assert rel_err(to_f64(y1), oracle()) <= 1e-4
+    assert not torch.allclose(y0, y1)
