@@ -5,7 +5,10 @@
 #include <cstring>
 #include <string>
 
+#include <vector>
+
 #include "../../include/sk.h"
+#include "../../include/sk_debug.h"
 #include "sk_launch.h"
 
 // Scratch of sk_linear_bwd_weight_noalloc (SK_NOALLOC_SCRATCH_BYTES, include/sk.h): device
@@ -23,6 +26,46 @@ constexpr size_t WS_ALIGN = 256;
 
 thread_local std::string g_hip_error;
 std::atomic<int> g_plan{0};
+
+// Forced plan parameters (sk_set_tuning; negative = the planner chooses).
+std::atomic<int> g_tune[SK_TUNE_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+int tune(sk_tune_knob knob) { return g_tune[knob].load(std::memory_order_relaxed); }
+
+// The calling thread's launch trace or kernel timer (include/sk_debug.h); null otherwise.
+struct Hooks : LaunchHooks {
+  bool trace = false;
+  std::vector<sk_trace_access> accesses;
+  int launches = 0;
+  // profile mode
+  std::vector<hipEvent_t> events;       // 2 per kernel: before, after
+  std::vector<std::string> names;
+  std::vector<unsigned> groups;
+  int max_kernels = 0;
+  bool recording = false;               // the current launch got its `before` event
+
+  bool tracing() const override { return trace; }
+  void access(const void* p, uint64_t bytes, bool write) override {
+    sk_trace_access a;
+    a.address = (uint64_t)reinterpret_cast<uintptr_t>(p);
+    a.bytes = bytes;
+    a.write = write ? 1 : 0;
+    a.launch = launches;
+    accesses.push_back(a);
+  }
+  void launch_recorded() override { ++launches; }
+  void before(const char* name, unsigned g, hipStream_t s) override {
+    recording = (int)names.size() < max_kernels;
+    if (!recording) return;
+    if (hipEventRecord(events[2 * names.size()], s) != hipSuccess) { recording = false; return; }
+    names.push_back(name);
+    groups.push_back(g);
+  }
+  void after(hipStream_t s) override {
+    if (recording) (void)hipEventRecord(events[2 * names.size() - 1], s);
+    recording = false;
+  }
+};
+thread_local Hooks* g_hooks = nullptr;
 
 size_t align_up(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
 
@@ -55,6 +98,14 @@ sk_status check_shape(int64_t tokens, int64_t in, int64_t out, int32_t l, int32_
   return SK_OK;
 }
 
+}  // namespace
+
+namespace sk {
+LaunchHooks* launch_hooks() { return g_hooks; }
+}  // namespace sk
+
+namespace {
+
 // Tile choice for the general GEMM (measured on MI355X).  The 256 x 256 tile with eight
 // waves has the best steady state (fewest LDS instructions per MFMA) but a long prologue,
 // so it pays from a contraction of 512 on when its tiles fill the chip; 128 x 128 runs two work-groups per CU, which overlaps one
@@ -62,10 +113,7 @@ sk_status check_shape(int64_t tokens, int64_t in, int64_t out, int32_t l, int32_
 // every CU a work-group without being mostly padding, the smallest when the problem
 // cannot fill the chip.
 int choose_tile(int64_t M, int64_t N, int64_t K, int splits) {
-  if (const char* e = getenv("SK_TUNE_TILE")) {  // tuning experiments only
-    const int t = atoi(e);
-    if (t >= 0 && t < TILE_COUNT) return t;
-  }
+  if (const int t = tune(SK_TUNE_TILE); t >= 0 && t < TILE_COUNT) return t;  // forced (tests, sweeps)
   const int64_t m_cap = (M + 63) / 64 * 64, n_cap = (N + 63) / 64 * 64;
   static const int order[] = {TILE_256x256_W8, TILE_128x128, TILE_128x64, TILE_64x128, TILE_64x64};
   for (int i = 0; i < (int)(sizeof(order) / sizeof(order[0])); ++i) {
@@ -122,7 +170,7 @@ FirstPlan plan_first(int64_t M, int64_t N, int64_t K) {
     if (splits > 1) t += splits * (double)M * N * 8.0 / 4.0e12 + 5.0e-6;
     return t;
   };
-  if (getenv("SK_TUNE_TILE")) return f;  // a forced tile is taken as it is
+  if (tune(SK_TUNE_TILE) >= 0) return f;  // a forced tile is taken as it is
   const double t_plain = time_of(f.tile, 1, K);
   double best = t_plain * 0.9;
   static const int cand[] = {TILE_128x128, TILE_128x64, TILE_64x128};
@@ -215,10 +263,7 @@ TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tuna
       if (best_split(M, N, T, 128, 128, true).time < best_split(M, N, T, 128, 64, true).time)
         w.tile = TILE_128x128;
     }
-    if (const char* e = tunable ? getenv("SK_TUNE_WTILE") : nullptr) {  // tuning experiments only
-      const int t = atoi(e);
-      if (t >= 0 && t < TILE_COUNT) w.tile = t;
-    }
+    if (const int t = tunable ? tune(SK_TUNE_WTILE) : -1; t >= 0 && t < TILE_COUNT) w.tile = t;  // forced
     w.big_tile = w.tile == TILE_256x256_W8 || w.tile == TILE_256x256;
     tile_dims(w.tile, bm, bn);
   } else {
@@ -229,8 +274,8 @@ TokenPlan plan_tokens(int64_t M, int64_t N, int64_t T, sk_dtype dtype, bool tuna
   int64_t splits = c.splits, kps = c.kps;
   int64_t max_splits = (T + 255) / 256;
   if (max_splits > 32) max_splits = 32;
-  if (const char* e = tunable ? getenv("SK_TUNE_WSPLITS") : nullptr) {  // tuning experiments only
-    splits = atoi(e) < 1 ? 1 : (atoi(e) > max_splits ? max_splits : atoi(e));
+  if (const int f = tunable ? tune(SK_TUNE_WSPLITS) : -1; f >= 0) {  // forced (clamped to 1..max)
+    splits = f < 1 ? 1 : (f > max_splits ? max_splits : f);
     kps = ((T + splits - 1) / splits + 63) / 64 * 64;
     splits = (T + kps - 1) / kps;
   }
@@ -284,7 +329,7 @@ WeightPlan plan_weight(const Shape& s) {
     w.colsum_splits = (int)((s.T + rows - 1) / rows);
   }
   w.head_cols = 0;
-  if (w.own_colsum && splits > 1 && s.R <= 65535 && !getenv("SK_TUNE_WSPLITS")) {
+  if (w.own_colsum && splits > 1 && s.R <= 65535 && tune(SK_TUNE_WSPLITS) < 0) {
     // More tiles than CUs but fewer than two rounds (c4: 344 tiles of 256 x 256): a round of
     // whole-token tiles covering as many tile columns as fit, then the remaining columns
     // split over the tokens so that they fill one more, shorter round.  Against the even
@@ -332,10 +377,7 @@ ChainShape chain_shape(int64_t T, int64_t N, int R, bool share_cu) {
   // forward -14..16 % from 65536 tokens on, +17 % at 4096 tokens, where they double the
   // number of work-groups that repeat stage 1)
   c.bm = (R <= 128 && T >= 128 * (int64_t)NUM_CUS) ? 128 : 64;
-  if (const char* e = getenv("SK_TUNE_BM")) {  // tuning experiments and tests only
-    const int v = atoi(e);
-    if (v == 64 || (v == 128 && R <= 128)) c.bm = v;
-  }
+  if (const int v = tune(SK_TUNE_BM); v == 64 || (v == 128 && R <= 128)) c.bm = v;  // forced
   const int64_t tiles_m = (T + c.bm - 1) / c.bm;
   const int64_t n_tiles = (N + chain_bn(R) - 1) / chain_bn(R);
   int64_t sl = NUM_CUS / tiles_m;
@@ -348,7 +390,7 @@ ChainShape chain_shape(int64_t T, int64_t N, int R, bool share_cu) {
   // and the stores crawl ([65536 x 8192 -> 8192], R = 128: forward 1030 us with one run of
   // 64 tiles per token tile, 550 us with four runs of 16)
   if (sl < (n_tiles + 23) / 24) sl = (n_tiles + 23) / 24;
-  if (const char* e = getenv("SK_TUNE_SLICES")) sl = atoi(e);  // tuning experiments only (clamped below)
+  if (const int v = tune(SK_TUNE_SLICES); v >= 0) sl = v;  // forced (clamped below)
   if (sl > n_tiles) sl = n_tiles;
   if (sl < 1) sl = 1;
   c.slices = (int)sl;
@@ -392,10 +434,9 @@ struct SketchPlan {
 SketchPlan plan_sketch(const Shape& s, int64_t K) {
   SketchPlan q{};
   q.tile = s.R <= 64 ? TILE_64x64 : (s.R <= 256 ? TILE_64x128 : TILE_128x128);
-  if (const char* e = getenv("SK_TUNE_STILE")) {  // tuning experiments only
-    const int t = atoi(e);
-    if (t == TILE_64x64 || t == TILE_64x128 || t == TILE_128x128 || t == TILE_128x64) q.tile = t;
-  }
+  if (const int t = tune(SK_TUNE_STILE);  // forced
+      t == TILE_64x64 || t == TILE_64x128 || t == TILE_128x128 || t == TILE_128x64)
+    q.tile = t;
   int bm, bn;
   tile_dims(q.tile, bm, bn);
   const int64_t tiles = ((s.T + bm - 1) / bm) * ((s.R + bn - 1) / bn);
@@ -404,7 +445,7 @@ SketchPlan plan_sketch(const Shape& s, int64_t K) {
   // two (8192-wide layer, R = 16: forward 36.8 -> 33.5 us)
   const int64_t want = s.R <= 64 ? 2 * NUM_CUS : NUM_CUS;
   int64_t splits = (want + tiles - 1) / tiles;
-  if (const char* e = getenv("SK_TUNE_SSPLITS")) splits = atoi(e);  // tuning experiments only (clamped below)
+  if (const int v = tune(SK_TUNE_SSPLITS); v >= 0) splits = v;  // forced (clamped below)
   const int64_t max_splits = K / 128 > 0 ? K / 128 : 1;   // at least two k chunks each
   if (splits > max_splits) splits = max_splits;
   if (splits > 8) splits = 8;
@@ -538,6 +579,68 @@ const char* sk_last_hip_error(void) { return g_hip_error.c_str(); }
 int sk_set_plan(int plan) {
   if (plan < 0 || plan > 3) return -1;
   return g_plan.exchange(plan);
+}
+
+int32_t sk_set_tuning(sk_tune_knob knob, int32_t value) {
+  if ((int)knob < 0 || (int)knob >= SK_TUNE_COUNT) return INT32_MIN;
+  return g_tune[knob].exchange(value < 0 ? -1 : value);
+}
+
+void sk_trace_begin(void) {
+  delete g_hooks;
+  g_hooks = new Hooks();
+  g_hooks->trace = true;
+}
+
+int64_t sk_trace_end(sk_trace_access* out, int64_t max, int32_t* launches) {
+  if (g_hooks == nullptr || !g_hooks->trace) return 0;
+  const int64_t n = (int64_t)g_hooks->accesses.size();
+  for (int64_t i = 0; i < n && i < max && out != nullptr; ++i) out[i] = g_hooks->accesses[i];
+  if (launches != nullptr) *launches = g_hooks->launches;
+  delete g_hooks;
+  g_hooks = nullptr;
+  return n;
+}
+
+int32_t sk_profile_begin(int32_t max_kernels) {
+  delete g_hooks;
+  g_hooks = nullptr;
+  if (max_kernels < 1) return -1;
+  Hooks* h = new Hooks();
+  h->max_kernels = max_kernels;
+  h->events.resize(2 * (size_t)max_kernels);
+  for (size_t i = 0; i < h->events.size(); ++i) {
+    if (hipEventCreate(&h->events[i]) != hipSuccess) {
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(h->events[j]);
+      delete h;
+      return -2;
+    }
+  }
+  g_hooks = h;
+  return 0;
+}
+
+int32_t sk_profile_end(sk_kernel_time* out, int32_t max) {
+  Hooks* h = g_hooks;
+  if (h == nullptr || h->trace) return -1;
+  g_hooks = nullptr;
+  const int32_t n = (int32_t)h->names.size();
+  int32_t rc = n;
+  if (n > 0 && hipEventSynchronize(h->events[2 * (size_t)n - 1]) != hipSuccess) rc = -3;
+  for (int32_t i = 0; rc >= 0 && i < n && i < max && out != nullptr; ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, h->events[2 * (size_t)i], h->events[2 * (size_t)i + 1]) != hipSuccess) {
+      rc = -4;
+      break;
+    }
+    strncpy(out[i].name, h->names[i].c_str(), sizeof(out[i].name) - 1);
+    out[i].name[sizeof(out[i].name) - 1] = 0;
+    out[i].ms = ms;
+    out[i].groups = (int32_t)h->groups[i];
+  }
+  for (hipEvent_t e : h->events) (void)hipEventDestroy(e);
+  delete h;
+  return rc;
 }
 
 size_t sk_linear_workspace_bytes(sk_op op, int64_t tokens, int64_t in, int64_t out, int32_t l,

@@ -3,12 +3,15 @@
 //
 //   C[M, N] = scale * (A . B) (+ bias[n]),   or raw fp32 split-K partial slabs.
 //
-// One work-group of 256 threads (4 waves, 2 x 2) owns a BM x BN tile; each wave
-// a (BM/2) x (BN/2) sub-tile of 32x32 MFMA blocks.  Operands go global ->
-// registers -> LDS (double buffered, one barrier per 64-wide k chunk) and are
-// read from LDS directly in the MFMA fragment layout; operands whose contiguous
-// dimension is not k are read with the LDS transpose read.  The result tile is
-// re-laid out through LDS so that global stores are whole contiguous rows.
+// One work-group of WAVES_M x WAVES_N waves (2 x 2, or 2 x 4 for the eight-wave
+// 256 x 256 tile) owns a BM x BN tile; each wave a (BM/WAVES_M) x (BN/WAVES_N)
+// sub-tile of 32x32 MFMA blocks.  Operands go global -> registers -> LDS (double
+// buffered, one barrier per 64-wide k chunk) and are read from LDS directly in the
+// MFMA fragment layout; operands whose contiguous dimension is not k are read with
+// the LDS transpose read.  Results leave straight from registers: fp32 as 16-byte
+// pieces, bf16 after a half-wave exchange that gives each lane eight consecutive
+// columns (no LDS re-layout).  Eight-wave launches with more tiles than CUs run as a
+// crew of one work-group per CU that walks the tiles.
 #include "sk_bf16_tile.h"
 #include "sk_launch.h"
 
@@ -398,23 +401,29 @@ __global__ __launch_bounds__(256) void reduce_to_bf16_kernel(const float* __rest
   *reinterpret_cast<uint2*>(out + i4) = w;
 }
 
+template <typename OutT>
+static std::string out_label() { return sizeof(OutT) == 2 ? "bf16" : "float"; }
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KC, bool B_KC, typename OutT, bool COLSUM>
 static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   a.tiles_m = (a.M + BM - 1) / BM;
   a.tiles_n = (a.N + BN - 1) / BN;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  note_gemm(a, A_KC, B_KC, 2, sizeof(OutT), sizeof(OutT) == 4);
   // big per-wave tiles have no registers to spare for a second set of loads in flight
   constexpr int PF = (BM * BN / (WAVES_M * WAVES_N) >= 128 * 64) ? 1 : 2;
+  const auto params = {lbl(BM), lbl(BN), lbl(WAVES_M), lbl(WAVES_N), lbl(A_KC), lbl(B_KC), out_label<OutT>(),
+                       lbl(COLSUM), lbl(PF)};
   if constexpr (PF == 1 && !COLSUM && WAVES_M * WAVES_N == 8) if (grid > NUM_CUS && grid < 0x7fffffffLL - NUM_CUS) {
     // more tiles than CUs: one work-group per CU (the tile's LDS admits no second) walks them
-    hipLaunchKernelGGL((gemm_bf16_crew_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>),
-                       dim3((unsigned)NUM_CUS), dim3(64 * WAVES_M * WAVES_N), 0, s, a, (int)grid);
-    return hipGetLastError();
+    static const std::string name = kernel_label("gemm_bf16_crew_kernel", params);
+    return launch_kernel(name.c_str(), gemm_bf16_crew_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>,
+                         dim3((unsigned)NUM_CUS), dim3(64 * WAVES_M * WAVES_N), s, a, (int)grid);
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>),
-                     dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), 0, s, a);
-  return hipGetLastError();
+  static const std::string name = kernel_label("gemm_bf16_kernel", params);
+  return launch_kernel(name.c_str(), gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>,
+                       dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), s, a);
 }
 
 template <bool A_KC, bool B_KC, typename OutT, bool COLSUM>
@@ -560,6 +569,13 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
   const long long gb = (long long)b.tiles_m * b.tiles_n * b.splits;
   if (ga <= 0 || gb <= 0 || ga + gb > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(ga + gb)), block(256);
+  {
+    bool akc, bkc, f32;
+    gemm_kind_traits(kind_a, akc, bkc, f32);
+    note_gemm(a, akc, bkc, 2, f32 ? 4 : 2, f32);
+    gemm_kind_traits(kind_b, akc, bkc, f32);
+    note_gemm(b, akc, bkc, 2, f32 ? 4 : 2, f32);
+  }
   typedef GemmTile<64, 128, 2, 2, true, true, float, false, 2> NTF_64x128;
   typedef GemmTile<64, 64, 2, 2, true, true, float, false, 2> NTF_64x64;
   typedef GemmTile<64, 64, 2, 2, false, true, bf16, false, 2> TT_64x64;
@@ -569,17 +585,17 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
   typedef GemmTile<128, 128, 2, 2, true, false, float, true, 2> NNFC_128x128;
   typedef GemmTile<64, 64, 2, 2, true, true, bf16, false, 2> NT_64x64;
   typedef GemmTile<128, 64, 2, 2, true, true, bf16, false, 2> NT_128x64;
+  const char* name = "dual_gemm_kernel";
   switch (pair) {
-    case 0: hipLaunchKernelGGL((dual_gemm_kernel<NTF_64x128, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
-    case 1: hipLaunchKernelGGL((dual_gemm_kernel<NTF_64x64, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
-    case 2: hipLaunchKernelGGL((dual_gemm_kernel<NT_128x128, TT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
-    case 3: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x64, NT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
-    case 4: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x128, NT_128x128>), grid, block, 0, s, a, b, (int)ga); break;
-    case 5: hipLaunchKernelGGL((dual_gemm_kernel<NT_64x64, TT_64x64>), grid, block, 0, s, a, b, (int)ga); break;
-    case 6: hipLaunchKernelGGL((dual_gemm_kernel<NNFC_128x64, NT_128x64>), grid, block, 0, s, a, b, (int)ga); break;
+    case 0: return launch_kernel(name, dual_gemm_kernel<NTF_64x128, TT_64x64>, grid, block, s, a, b, (int)ga);
+    case 1: return launch_kernel(name, dual_gemm_kernel<NTF_64x64, TT_64x64>, grid, block, s, a, b, (int)ga);
+    case 2: return launch_kernel(name, dual_gemm_kernel<NT_128x128, TT_128x128>, grid, block, s, a, b, (int)ga);
+    case 3: return launch_kernel(name, dual_gemm_kernel<NNFC_128x64, NT_128x128>, grid, block, s, a, b, (int)ga);
+    case 4: return launch_kernel(name, dual_gemm_kernel<NNFC_128x128, NT_128x128>, grid, block, s, a, b, (int)ga);
+    case 5: return launch_kernel(name, dual_gemm_kernel<NT_64x64, TT_64x64>, grid, block, s, a, b, (int)ga);
+    case 6: return launch_kernel(name, dual_gemm_kernel<NNFC_128x64, NT_128x64>, grid, block, s, a, b, (int)ga);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_gemm_f32slabs_with_colsum(int tile, GemmArgs a, const void* in, float* out, int rows,
@@ -593,17 +609,21 @@ hipError_t launch_gemm_f32slabs_with_colsum(int tile, GemmArgs a, const void* in
   const long long gg = (long long)a.tiles_m * a.tiles_n * a.splits;
   const long long grid = gg + (long long)c.col_groups * splits;
   if (gg <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>),
-                     dim3((unsigned)grid), dim3(512), 0, s, a, (int)gg, c);
-  return hipGetLastError();
+  note_gemm(a, true, false, 2, 4, true);
+  note_matrix(in, rows, cols, cols, 2, false);
+  note_matrix(out, splits, cols, cols, 4, true);
+  return launch_kernel("gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>",
+                       gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>,
+                       dim3((unsigned)grid), dim3(512), s, a, (int)gg, c);
 }
 
 hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, int splits,
                               int rows_per_split, hipStream_t s) {
   const dim3 grid((unsigned)((cols + COLSUM_COLS - 1) / COLSUM_COLS), (unsigned)splits);
-  hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(256), 0, s,
-                     static_cast<const unsigned short*>(in), out, rows, cols, rows_per_split);
-  return hipGetLastError();
+  note_matrix(in, rows, cols, cols, 2, false);
+  note_matrix(out, splits, cols, cols, 4, true);
+  return launch_kernel("colsum_bf16_kernel", colsum_bf16_kernel, grid, dim3(256), s,
+                       static_cast<const unsigned short*>(in), out, rows, cols, rows_per_split);
 }
 
 __global__ __launch_bounds__(256) void reduce_splits_2d_kernel(const float* __restrict__ part,
@@ -627,25 +647,27 @@ hipError_t launch_reduce_splits_2d(const float* part, float* out, int rows, int 
                                    int splits, float scale, hipStream_t s) {
   if (rows < 1 || rows > 65535 || cols < 4 || (cols & 3) != 0 || splits < 1) return hipErrorInvalidValue;
   const dim3 grid((unsigned)((cols / 4 + 255) / 256), (unsigned)rows);
-  hipLaunchKernelGGL(reduce_splits_2d_kernel, grid, dim3(256), 0, s, part, out, rows, cols, ld_out, splits,
-                     scale);
-  return hipGetLastError();
+  note_matrix(part, (int64_t)splits * rows, cols, cols, 4, false);
+  note_matrix(out, rows, cols, ld_out, 4, true);
+  return launch_kernel("reduce_splits_2d_kernel", reduce_splits_2d_kernel, grid, dim3(256), s, part, out, rows,
+                       cols, ld_out, splits, scale);
 }
 
 hipError_t launch_reduce_to_bf16(const float* part, void* out, int64_t n, int splits, hipStream_t s) {
   if (n <= 0 || (n & 3) != 0 || splits < 1) return hipErrorInvalidValue;
   const int64_t groups = (n / 4 + 255) / 256;
   if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(reduce_to_bf16_kernel, dim3((unsigned)groups), dim3(256), 0, s, part,
-                     static_cast<bf16*>(out), n, splits);
-  return hipGetLastError();
+  note_matrix(part, splits, n, n, 4, false);
+  note_matrix(out, 1, n, n, 2, true);
+  return launch_kernel("reduce_to_bf16_kernel", reduce_to_bf16_kernel, dim3((unsigned)groups), dim3(256), s,
+                       part, static_cast<bf16*>(out), n, splits);
 }
 
 hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s) {
   const int64_t groups = ((a.n + a.n2) / 4 + 255) / 256;
   if (groups <= 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)groups), dim3(256), 0, s, a);
-  return hipGetLastError();
+  note_reduce(a);
+  return launch_kernel("reduce_splits_kernel", reduce_splits_kernel, dim3((unsigned)groups), dim3(256), s, a);
 }
 
 }  // namespace sk

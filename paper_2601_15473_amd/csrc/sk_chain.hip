@@ -10,11 +10,13 @@
 // A work-group (256 threads, 4 waves) owns one token tile and one slice of the N
 // range.  Zt sits in LDS once and every wave lifts the whole of it into registers
 // as MFMA fragments; the waves then split each BN-wide tile of N four ways, so a B2
-// fragment is read from LDS by exactly one wave and used for both 32-row blocks.
-// B2 streams through a double-buffered LDS chunk (64 of the R rows at a time)
-// across tile boundaries, so the load of the next tile overlaps the MFMAs and the
-// stores of the current one.  Output tiles leave through an LDS re-layout as whole
-// 2*BN-byte rows.
+// fragment is read from LDS by exactly one wave and used for all 32-row blocks.
+// Two kernels share that plan:
+//   chain_small_kernel (R <= 128, the one the automatic plans use): B2 arrives one whole
+//     [R x 128] tile at a time, double buffered across tile boundaries, and output rows
+//     leave straight from registers as 16-byte pieces (no LDS re-layout);
+//   chain_kernel (R <= 512, forced plans only): B2 streams in 64-row chunks and the output
+//     tile is re-laid out through LDS into whole rows.
 #include "sk_bf16_tile.h"
 #include "sk_launch.h"
 
@@ -632,18 +634,20 @@ template <int RT, int BN, bool B2_KC, bool FUSED, bool B1_KC>
 static hipError_t launch_one(const ChainArgs& a, hipStream_t s) {
   const long long grid = (long long)a.tiles_m * a.n_slices;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((chain_kernel<RT, BN, B2_KC, FUSED, B1_KC>), dim3((unsigned)grid), dim3(256), 0,
-                     s, a);
-  return hipGetLastError();
+  static const std::string name =
+      kernel_label("chain_kernel", {lbl(RT), lbl(BN), lbl(B2_KC), lbl(FUSED), lbl(B1_KC)});
+  return launch_kernel(name.c_str(), chain_kernel<RT, BN, B2_KC, FUSED, B1_KC>, dim3((unsigned)grid), dim3(256),
+                       s, a);
 }
 
 template <int MB, int RT, bool B2_KC, bool FUSED, bool B1_KC>
 static hipError_t launch_small_mb(const ChainArgs& a, hipStream_t s) {
   const long long grid = (long long)a.tiles_m * a.n_slices;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((chain_small_kernel<MB, RT, B2_KC, FUSED, B1_KC>), dim3((unsigned)grid),
-                     dim3(256), 0, s, a);
-  return hipGetLastError();
+  static const std::string name =
+      kernel_label("chain_small_kernel", {lbl(MB), lbl(RT), lbl(B2_KC), lbl(FUSED), lbl(B1_KC)});
+  return launch_kernel(name.c_str(), chain_small_kernel<MB, RT, B2_KC, FUSED, B1_KC>, dim3((unsigned)grid),
+                       dim3(256), s, a);
 }
 
 template <int RT, bool B2_KC, bool FUSED, bool B1_KC>
@@ -675,6 +679,20 @@ hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s) 
   if (a.bm == 0) a.bm = CH_BM;
   if (a.bm != CH_BM && !(a.bm == 128 && a.R <= 128)) return hipErrorInvalidValue;
   a.tiles_m = (a.M + a.bm - 1) / a.bm;
+  if (tracing()) {
+    if (fused) {
+      note_matrix(a.A, a.M, a.K1, a.lda, 2, false);
+      note_matrix(a.B1, b_kc ? a.R : a.K1, b_kc ? a.K1 : a.R, a.ldb1, 2, false);
+    } else if (a.z_splits == 0) {
+      note_matrix(a.Z, a.M, a.R, a.R, 2, false);
+    } else {   // fp32 slabs [M, R], z_slab elements apart
+      note_matrix(a.Z, 1, (int64_t)(a.z_splits - 1) * a.z_slab + (int64_t)a.M * a.R, 0, 4, false);
+    }
+    note_matrix(a.B2, b_kc ? a.N : a.R, b_kc ? a.R : a.N, a.ldb2, 2, false);
+    if (a.bias != nullptr) note_matrix(a.bias, 1, a.N, a.N, 2, false);
+    note_matrix(a.C, a.M, a.N, a.ldc, 2, true);
+    note_reduce(a.tail);
+  }
   if (b_kc) return fused ? launch_rt<true, true>(a, s) : launch_rt<true, false>(a, s);
   return fused ? launch_rt<false, true>(a, s) : launch_rt<false, false>(a, s);
 }

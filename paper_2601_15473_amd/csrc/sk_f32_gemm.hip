@@ -152,11 +152,14 @@ static hipError_t launch_one(GemmArgs a, hipStream_t s) {
   a.tiles_n = (a.N + bmn - 1) / bmn;
   const long long grid = (long long)a.tiles_m * a.tiles_n * a.splits;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (bmn == 128)
-    hipLaunchKernelGGL((gemm_f32_kernel<2, A_KC, B_KC, COLSUM>), dim3((unsigned)grid), dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL((gemm_f32_kernel<1, A_KC, B_KC, COLSUM>), dim3((unsigned)grid), dim3(256), 0, s, a);
-  return hipGetLastError();
+  // (the result is always addressed as slabs [M, ldc], one per k range: one slab when not split)
+  note_gemm(a, A_KC, B_KC, 4, 4, true);
+  if (bmn == 128) {
+    static const std::string name = kernel_label("gemm_f32_kernel", {lbl(2), lbl(A_KC), lbl(B_KC), lbl(COLSUM)});
+    return launch_kernel(name.c_str(), gemm_f32_kernel<2, A_KC, B_KC, COLSUM>, dim3((unsigned)grid), dim3(256), s, a);
+  }
+  static const std::string name = kernel_label("gemm_f32_kernel", {lbl(1), lbl(A_KC), lbl(B_KC), lbl(COLSUM)});
+  return launch_kernel(name.c_str(), gemm_f32_kernel<1, A_KC, B_KC, COLSUM>, dim3((unsigned)grid), dim3(256), s, a);
 }
 
 hipError_t launch_gemm_f32(GemmKind kind, const GemmArgs& a, hipStream_t s) {

@@ -1,8 +1,73 @@
 // Host-side launchers of libsk's kernels (internal; the public ABI is include/sk.h).
 #pragma once
+#include <string>
+#include <type_traits>
+
 #include "sk_common.h"
 
 namespace sk {
+
+// ---------------------------------------------------------------------------
+// Launch plumbing: every kernel of the library goes out through launch_kernel, which
+// reports the launch's own status (not a stale error some earlier HIP call of the process
+// left behind) and serves the two testing aids of include/sk_debug.h -- the host-only
+// launch trace and the per-kernel event timing.
+// ---------------------------------------------------------------------------
+struct LaunchHooks {
+  virtual ~LaunchHooks() {}
+  // trace mode: returns true when launches are to be recorded instead of made
+  virtual bool tracing() const = 0;
+  virtual void access(const void* p, uint64_t bytes, bool write) = 0;   // of the launch that follows
+  virtual void launch_recorded() = 0;
+  // profile mode: events around the launch
+  virtual void before(const char* name, unsigned groups, hipStream_t s) = 0;
+  virtual void after(hipStream_t s) = 0;
+};
+LaunchHooks* launch_hooks();   // the calling thread's, or null (the normal case)
+
+inline bool tracing() {
+  LaunchHooks* h = launch_hooks();
+  return h != nullptr && h->tracing();
+}
+// Byte range a kernel about to be launched reads or writes: a dense or strided matrix of
+// `rows` rows of `cols` elements, rows `ld` elements apart (from the first byte of the
+// first row to the last byte of the last row).  Recorded in trace mode only.
+inline void note_matrix(const void* p, int64_t rows, int64_t cols, int64_t ld, int esize, bool write) {
+  LaunchHooks* h = launch_hooks();
+  if (h == nullptr || !h->tracing() || p == nullptr || rows <= 0 || cols <= 0) return;
+  h->access(p, (uint64_t)(((rows - 1) * ld + cols) * esize), write);
+}
+
+template <typename... KArgs>
+inline hipError_t launch_kernel(const char* name, void (*kernel)(KArgs...), dim3 grid, dim3 block,
+                                hipStream_t s, typename std::common_type<KArgs>::type... args) {
+  LaunchHooks* h = launch_hooks();
+  if (h != nullptr && h->tracing()) {
+    h->launch_recorded();
+    return hipSuccess;
+  }
+  if (h != nullptr) h->before(name, grid.x * grid.y * grid.z, s);
+  void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, s);
+  if (h != nullptr) h->after(s);
+  return e;
+}
+
+// "kernel<256, 256, 2, 4, true, false, bf16, false, 1>": a template instance's name as a
+// profiler prints it.
+inline std::string kernel_label(const char* base, std::initializer_list<std::string> params) {
+  std::string n = base;
+  n += "<";
+  bool first = true;
+  for (const std::string& q : params) {
+    if (!first) n += ", ";
+    n += q;
+    first = false;
+  }
+  return n + ">";
+}
+inline std::string lbl(int v) { return std::to_string(v); }
+inline std::string lbl(bool v) { return v ? "true" : "false"; }
 
 enum GemmKind : int {
   GEMM_NN = 0,      // A [M,K], B [K,N]            -> storage type
@@ -15,6 +80,12 @@ enum GemmKind : int {
   GEMM_TN_F32_PLAIN = 7,   // as GEMM_TN_F32 without the column sums (any tile)
   GEMM_TT_F32 = 8,         // as GEMM_TT, split-K          -> fp32 slabs
 };
+
+inline void gemm_kind_traits(GemmKind kind, bool& a_kc, bool& b_kc, bool& out_f32) {
+  a_kc = !(kind == GEMM_TN_F32 || kind == GEMM_TN_F32_PLAIN || kind == GEMM_TT || kind == GEMM_TT_F32);
+  b_kc = kind == GEMM_NT || kind == GEMM_NT_F32 || kind == GEMM_TT || kind == GEMM_TT_F32;
+  out_f32 = !(kind == GEMM_NN || kind == GEMM_NT || kind == GEMM_TT);
+}
 
 enum TileCfg : int {
   TILE_256x256 = 0,
@@ -33,6 +104,30 @@ inline void tile_dims(int tile, int& bm, int& bn) {
                                           {64, 64},   {256, 128}, {128, 256}, {256, 256}};
   bm = dims[tile][0];
   bn = dims[tile][1];
+}
+
+// What a GEMM launch touches (trace mode): operands of `esize` bytes per element, result of
+// `osize` bytes; `slabs`: the result is `splits` slabs of [M, ldc], one per k range.
+inline void note_gemm(const GemmArgs& a, bool a_kc, bool b_kc, int esize, int osize, bool slabs) {
+  if (!tracing()) return;
+  note_matrix(a.A, a_kc ? a.M : a.K, a_kc ? a.K : a.M, a.lda, esize, false);
+  note_matrix(a.B, b_kc ? a.N : a.K, b_kc ? a.K : a.N, a.ldb, esize, false);
+  const int n_store = a.n_store > 0 ? a.n_store : a.N;
+  const int64_t rows = slabs ? (int64_t)(a.splits - 1) * a.M + a.M : a.M;
+  note_matrix(a.C, rows, n_store, a.ldc, osize, true);
+  if (a.bias != nullptr) note_matrix(a.bias, 1, a.N, a.N, esize, false);
+  if (a.colsum != nullptr) note_matrix(a.colsum, a.splits, a.N, a.N, 4, true);
+}
+inline void note_reduce(const ReduceArgs& r) {
+  if (!tracing()) return;
+  if (r.n > 0) {
+    note_matrix(r.part, r.splits, r.n, r.n, 4, false);
+    note_matrix(r.out, 1, r.n, r.n, 4, true);
+  }
+  if (r.n2 > 0) {
+    note_matrix(r.part2, r.splits2, r.n2, r.n2, 4, false);
+    note_matrix(r.out2, 1, r.n2, r.n2, 4, true);
+  }
 }
 
 // bf16 operands, fp32 accumulation (MFMA).  `tiles_m/tiles_n` of `a` are filled in here.

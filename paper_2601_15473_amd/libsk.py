@@ -64,6 +64,32 @@ _lib.sk_last_hip_error.argtypes = []
 _lib.sk_set_plan.restype = ctypes.c_int
 _lib.sk_set_plan.argtypes = [ctypes.c_int]
 
+# ---- testing / tuning / measurement aids (include/sk_debug.h) ----
+SK_TUNE_TILE, SK_TUNE_WTILE, SK_TUNE_WSPLITS, SK_TUNE_BM, SK_TUNE_SLICES, SK_TUNE_STILE, SK_TUNE_SSPLITS = range(7)
+
+
+class TraceAccess(ctypes.Structure):
+    _fields_ = [("address", ctypes.c_uint64), ("bytes", ctypes.c_uint64),
+                ("write", ctypes.c_int32), ("launch", ctypes.c_int32)]
+
+
+class KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 120), ("ms", ctypes.c_float), ("groups", ctypes.c_int32)]
+
+
+_lib.sk_set_tuning.restype = ctypes.c_int32
+_lib.sk_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int32]
+_lib.sk_trace_begin.restype = None
+_lib.sk_trace_begin.argtypes = []
+_lib.sk_trace_end.restype = ctypes.c_int64
+_lib.sk_trace_end.argtypes = [ctypes.POINTER(TraceAccess), ctypes.c_int64, ctypes.POINTER(ctypes.c_int32)]
+_lib.sk_profile_begin.restype = ctypes.c_int32
+_lib.sk_profile_begin.argtypes = [ctypes.c_int32]
+_lib.sk_profile_end.restype = ctypes.c_int32
+_lib.sk_profile_end.argtypes = [ctypes.POINTER(KernelTime), ctypes.c_int32]
+
+DEBUG_EXPORTS = ("sk_set_tuning", "sk_trace_begin", "sk_trace_end", "sk_profile_begin", "sk_profile_end")
+
 EXPORTS = ("sk_linear_fwd", "sk_linear_bwd_input", "sk_linear_bwd_weight", "sk_linear_bwd",
            "sk_linear_bwd_weight_first", "sk_linear_bwd_weight_noalloc",
            "sk_linear_workspace_bytes", "sk_status_string", "sk_last_hip_error", "sk_set_plan")
@@ -147,6 +173,42 @@ def sk_last_hip_error():
 
 def sk_set_plan(plan):
     return _lib.sk_set_plan(plan)
+
+
+def sk_set_tuning(knob, value):
+    """Force a plan parameter (value < 0: automatic again); returns the previous value."""
+    return _lib.sk_set_tuning(knob, value)
+
+
+def sk_trace_begin():
+    _lib.sk_trace_begin()
+
+
+_trace_buf = (TraceAccess * 256)()
+
+
+def sk_trace_end():
+    """-> (list of (address, bytes, write, launch), number of launches)."""
+    launches = ctypes.c_int32(0)
+    n = _lib.sk_trace_end(_trace_buf, len(_trace_buf), ctypes.byref(launches))
+    if n > len(_trace_buf):
+        raise RuntimeError(f"launch trace holds {n} records, buffer {len(_trace_buf)}")
+    return [(a.address, a.bytes, a.write, a.launch) for a in _trace_buf[:n]], launches.value
+
+
+def sk_profile_begin(max_kernels):
+    rc = _lib.sk_profile_begin(max_kernels)
+    if rc != 0:
+        raise RuntimeError(f"sk_profile_begin failed ({rc})")
+
+
+def sk_profile_end(max_kernels):
+    """-> list of (kernel name, ms, work-groups), one per launch, in launch order."""
+    buf = (KernelTime * max_kernels)()
+    n = _lib.sk_profile_end(buf, max_kernels)
+    if n < 0:
+        raise RuntimeError(f"sk_profile_end failed ({n})")
+    return [(k.name.decode(), float(k.ms), int(k.groups)) for k in buf[:min(n, max_kernels)]]
 
 
 def check(status):

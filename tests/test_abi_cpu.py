@@ -19,6 +19,13 @@ def test_every_declared_symbol_is_exported():
     assert declared == set(sk.EXPORTS)
     for name in declared:
         assert hasattr(sk._lib, name), name
+    # the testing / measurement aids have a header of their own
+    dbg = open(os.path.join(ROOT, "include", "sk_debug.h")).read()
+    dbg = re.sub(r"/\*.*?\*/", "", dbg, flags=re.S)
+    declared = set(re.findall(r"\b(sk_[a-z_]+)\s*\(", dbg))
+    assert declared == set(sk.DEBUG_EXPORTS)
+    for name in declared:
+        assert hasattr(sk._lib, name), name
 
 
 def test_status_strings():

@@ -23,6 +23,19 @@ def sk():
     libsk.sk_set_plan(0)
 
 
+@pytest.fixture
+def tuning(sk):
+    """Forces plan parameters for one test: tuning(knob, value); all automatic again afterwards."""
+    touched = []
+
+    def force(knob, value):
+        touched.append(knob)
+        sk.sk_set_tuning(knob, value)
+    yield force
+    for knob in touched:
+        sk.sk_set_tuning(knob, -1)
+
+
 def oracle_all(t: W.Tensors):
     v = {n: a.astype(np.float64) for n, a in t.value.items()}
     b = v.get("b")
@@ -253,13 +266,13 @@ def test_random_shapes(sk, w):
         assert rel_err(to_f64(got), want[n]) <= TOL[w.dtype], n
 
 
-def test_forced_big_tiles(sk, monkeypatch):
+def test_forced_big_tiles(sk, tuning):
     """The large-shape code paths (big tiles, the bias gradient from its own kernel)
     on a shape small enough for a full oracle pass."""
     w = W.Workload("bf16_forced_paths", 700, 320, 592, 2, 72, "bf16", seed=10)
     for tile, wtile in ((7, 7), (0, 5), (5, 1), (6, 2)):
-        monkeypatch.setenv("SK_TUNE_TILE", str(tile))
-        monkeypatch.setenv("SK_TUNE_WTILE", str(wtile))
+        tuning(sk.SK_TUNE_TILE, tile)
+        tuning(sk.SK_TUNE_WTILE, wtile)
         check_all(sk, w, 2)
 
 
@@ -274,11 +287,11 @@ TALL_CASES = [
 
 @pytest.mark.parametrize("w", TALL_CASES, ids=lambda w: f"{w.name}_T{w.tokens}")
 @pytest.mark.parametrize("plan", [1, 3], ids=["fused", "split_expand"])
-def test_tall_token_tiles_forced(sk, monkeypatch, w, plan):
+def test_tall_token_tiles_forced(sk, tuning, w, plan):
     """The 128-row token tiles of the narrow kernels (picked by themselves only from 32768
     tokens on), forced onto shapes small and ragged enough for a full oracle pass: three
     calls and the single-call backward."""
-    monkeypatch.setenv("SK_TUNE_BM", "128")
+    tuning(sk.SK_TUNE_BM, 128)
     check_all(sk, w, plan)
     sk.sk_set_plan(0)
     t = W.generate(w)
