@@ -819,6 +819,7 @@ sk_status sk_linear_bwd_weight(const void* x, const void* S_cat, const void* dY,
       a.B = static_cast<const unsigned char*>(dY) + (size_t)w.head_cols * s.esize;
       a.N = (int)out - w.head_cols; a.ldc = a.N; a.C = part; a.colsum = nullptr; a.scale = 1.0f;
     }
+    a.colsum = nullptr;   // (the big tiles have no column-sum epilogue: that is what the kernel above is for)
     if (ride)
       e = launch_gemm_f32slabs_with_colsum(w.tile, a, dY, w.colsum_splits == 1 ? dbias : cpart, (int)tokens,
                                            (int)out, w.colsum_splits, w.colsum_rows, hs);
