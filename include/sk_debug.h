@@ -72,6 +72,9 @@ typedef struct {
   char name[120];
   float ms;
   int32_t groups;    /* work-groups in the launch */
+  double flops;      /* flops of the products the launch forms (2 M N K per contraction) */
+  double bytes;      /* bytes it must move: each operand read once, each result written once
+                        (re-reads across tiles and cache traffic not counted) */
 } sk_kernel_time;
 
 /* Returns 0, or a negative value if the events could not be created (nothing is then recorded). */

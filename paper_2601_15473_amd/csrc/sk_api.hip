@@ -40,6 +40,7 @@ struct Hooks : LaunchHooks {
   std::vector<hipEvent_t> events;       // 2 per kernel: before, after
   std::vector<std::string> names;
   std::vector<unsigned> groups;
+  std::vector<Work> work;
   int max_kernels = 0;
   bool recording = false;               // the current launch got its `before` event
 
@@ -53,12 +54,13 @@ struct Hooks : LaunchHooks {
     accesses.push_back(a);
   }
   void launch_recorded() override { ++launches; }
-  void before(const char* name, unsigned g, hipStream_t s) override {
+  void before(const char* name, unsigned g, double flops, double bytes, hipStream_t s) override {
     recording = (int)names.size() < max_kernels;
     if (!recording) return;
     if (hipEventRecord(events[2 * names.size()], s) != hipSuccess) { recording = false; return; }
     names.push_back(name);
     groups.push_back(g);
+    work.push_back(Work{flops, bytes});
   }
   void after(hipStream_t s) override {
     if (recording) (void)hipEventRecord(events[2 * names.size() - 1], s);
@@ -637,6 +639,8 @@ int32_t sk_profile_end(sk_kernel_time* out, int32_t max) {
     out[i].name[sizeof(out[i].name) - 1] = 0;
     out[i].ms = ms;
     out[i].groups = (int32_t)h->groups[i];
+    out[i].flops = h->work[i].flops;
+    out[i].bytes = h->work[i].bytes;
   }
   for (hipEvent_t e : h->events) (void)hipEventDestroy(e);
   delete h;

@@ -418,11 +418,11 @@ static hipError_t launch_cfg(GemmArgs a, hipStream_t s) {
   if constexpr (PF == 1 && !COLSUM && WAVES_M * WAVES_N == 8) if (grid > NUM_CUS && grid < 0x7fffffffLL - NUM_CUS) {
     // more tiles than CUs: one work-group per CU (the tile's LDS admits no second) walks them
     static const std::string name = kernel_label("gemm_bf16_crew_kernel", params);
-    return launch_kernel(name.c_str(), gemm_bf16_crew_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>,
+    return launch_kernel(name.c_str(), gemm_work(a, 2, sizeof(OutT), sizeof(OutT) == 4), gemm_bf16_crew_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>,
                          dim3((unsigned)NUM_CUS), dim3(64 * WAVES_M * WAVES_N), s, a, (int)grid);
   }
   static const std::string name = kernel_label("gemm_bf16_kernel", params);
-  return launch_kernel(name.c_str(), gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>,
+  return launch_kernel(name.c_str(), gemm_work(a, 2, sizeof(OutT), sizeof(OutT) == 4), gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>,
                        dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), s, a);
 }
 
@@ -569,12 +569,17 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
   const long long gb = (long long)b.tiles_m * b.tiles_n * b.splits;
   if (ga <= 0 || gb <= 0 || ga + gb > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(ga + gb)), block(256);
+  Work work;
   {
     bool akc, bkc, f32;
     gemm_kind_traits(kind_a, akc, bkc, f32);
     note_gemm(a, akc, bkc, 2, f32 ? 4 : 2, f32);
+    work = gemm_work(a, 2, f32 ? 4 : 2, f32);
     gemm_kind_traits(kind_b, akc, bkc, f32);
     note_gemm(b, akc, bkc, 2, f32 ? 4 : 2, f32);
+    const Work wb = gemm_work(b, 2, f32 ? 4 : 2, f32);
+    work.flops += wb.flops;
+    work.bytes += wb.bytes;
   }
   typedef GemmTile<64, 128, 2, 2, true, true, float, false, 2> NTF_64x128;
   typedef GemmTile<64, 64, 2, 2, true, true, float, false, 2> NTF_64x64;
@@ -587,13 +592,13 @@ hipError_t launch_dual_gemm_bf16(GemmKind kind_a, int tile_a, GemmArgs a, GemmKi
   typedef GemmTile<128, 64, 2, 2, true, true, bf16, false, 2> NT_128x64;
   const char* name = "dual_gemm_kernel";
   switch (pair) {
-    case 0: return launch_kernel(name, dual_gemm_kernel<NTF_64x128, TT_64x64>, grid, block, s, a, b, (int)ga);
-    case 1: return launch_kernel(name, dual_gemm_kernel<NTF_64x64, TT_64x64>, grid, block, s, a, b, (int)ga);
-    case 2: return launch_kernel(name, dual_gemm_kernel<NT_128x128, TT_128x128>, grid, block, s, a, b, (int)ga);
-    case 3: return launch_kernel(name, dual_gemm_kernel<NNFC_128x64, NT_128x128>, grid, block, s, a, b, (int)ga);
-    case 4: return launch_kernel(name, dual_gemm_kernel<NNFC_128x128, NT_128x128>, grid, block, s, a, b, (int)ga);
-    case 5: return launch_kernel(name, dual_gemm_kernel<NT_64x64, TT_64x64>, grid, block, s, a, b, (int)ga);
-    case 6: return launch_kernel(name, dual_gemm_kernel<NNFC_128x64, NT_128x64>, grid, block, s, a, b, (int)ga);
+    case 0: return launch_kernel(name, work, dual_gemm_kernel<NTF_64x128, TT_64x64>, grid, block, s, a, b, (int)ga);
+    case 1: return launch_kernel(name, work, dual_gemm_kernel<NTF_64x64, TT_64x64>, grid, block, s, a, b, (int)ga);
+    case 2: return launch_kernel(name, work, dual_gemm_kernel<NT_128x128, TT_128x128>, grid, block, s, a, b, (int)ga);
+    case 3: return launch_kernel(name, work, dual_gemm_kernel<NNFC_128x64, NT_128x128>, grid, block, s, a, b, (int)ga);
+    case 4: return launch_kernel(name, work, dual_gemm_kernel<NNFC_128x128, NT_128x128>, grid, block, s, a, b, (int)ga);
+    case 5: return launch_kernel(name, work, dual_gemm_kernel<NT_64x64, TT_64x64>, grid, block, s, a, b, (int)ga);
+    case 6: return launch_kernel(name, work, dual_gemm_kernel<NNFC_128x64, NT_128x64>, grid, block, s, a, b, (int)ga);
     default: return hipErrorInvalidValue;
   }
 }
@@ -612,7 +617,9 @@ hipError_t launch_gemm_f32slabs_with_colsum(int tile, GemmArgs a, const void* in
   note_gemm(a, true, false, 2, 4, true);
   note_matrix(in, rows, cols, cols, 2, false);
   note_matrix(out, splits, cols, cols, 4, true);
-  return launch_kernel("gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>",
+  Work work = gemm_work(a, 2, 4, true);
+  work.bytes += (double)rows * cols * 2 + (double)splits * cols * 4;
+  return launch_kernel("gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>", work,
                        gemm_bf16_with_colsum_kernel<256, 256, 2, 4, true, false, float, 1>,
                        dim3((unsigned)grid), dim3(512), s, a, (int)gg, c);
 }
@@ -622,7 +629,8 @@ hipError_t launch_colsum_bf16(const void* in, float* out, int rows, int cols, in
   const dim3 grid((unsigned)((cols + COLSUM_COLS - 1) / COLSUM_COLS), (unsigned)splits);
   note_matrix(in, rows, cols, cols, 2, false);
   note_matrix(out, splits, cols, cols, 4, true);
-  return launch_kernel("colsum_bf16_kernel", colsum_bf16_kernel, grid, dim3(256), s,
+  return launch_kernel("colsum_bf16_kernel", Work{0.0, (double)rows * cols * 2 + (double)splits * cols * 4},
+                       colsum_bf16_kernel, grid, dim3(256), s,
                        static_cast<const unsigned short*>(in), out, rows, cols, rows_per_split);
 }
 
@@ -649,7 +657,7 @@ hipError_t launch_reduce_splits_2d(const float* part, float* out, int rows, int 
   const dim3 grid((unsigned)((cols / 4 + 255) / 256), (unsigned)rows);
   note_matrix(part, (int64_t)splits * rows, cols, cols, 4, false);
   note_matrix(out, rows, cols, ld_out, 4, true);
-  return launch_kernel("reduce_splits_2d_kernel", reduce_splits_2d_kernel, grid, dim3(256), s, part, out, rows,
+  return launch_kernel("reduce_splits_2d_kernel", Work{0.0, 4.0 * rows * cols * (splits + 1)}, reduce_splits_2d_kernel, grid, dim3(256), s, part, out, rows,
                        cols, ld_out, splits, scale);
 }
 
@@ -659,7 +667,7 @@ hipError_t launch_reduce_to_bf16(const float* part, void* out, int64_t n, int sp
   if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
   note_matrix(part, splits, n, n, 4, false);
   note_matrix(out, 1, n, n, 2, true);
-  return launch_kernel("reduce_to_bf16_kernel", reduce_to_bf16_kernel, dim3((unsigned)groups), dim3(256), s,
+  return launch_kernel("reduce_to_bf16_kernel", Work{0.0, (double)n * (4.0 * splits + 2.0)}, reduce_to_bf16_kernel, dim3((unsigned)groups), dim3(256), s,
                        part, static_cast<bf16*>(out), n, splits);
 }
 
@@ -667,7 +675,7 @@ hipError_t launch_reduce_splits(const ReduceArgs& a, hipStream_t s) {
   const int64_t groups = ((a.n + a.n2) / 4 + 255) / 256;
   if (groups <= 0) return hipSuccess;
   note_reduce(a);
-  return launch_kernel("reduce_splits_kernel", reduce_splits_kernel, dim3((unsigned)groups), dim3(256), s, a);
+  return launch_kernel("reduce_splits_kernel", reduce_work(a), reduce_splits_kernel, dim3((unsigned)groups), dim3(256), s, a);
 }
 
 }  // namespace sk

@@ -630,13 +630,26 @@ __global__ __launch_bounds__(256) void chain_small_kernel(const ChainArgs p) {
 
 bool chain_supported(int R) { return R >= 16 && R <= 512; }
 
+// Flops and bytes of a chain launch: both contractions when the first one is fused in,
+// otherwise the second one with the intermediate (or its slabs) read from memory; the
+// reduction it may carry along counts by its bytes.
+static Work chain_work(const ChainArgs& a, bool fused) {
+  Work w;
+  w.flops = 2.0 * a.M * a.R * ((fused ? a.K1 : 0) + (double)a.N);
+  w.bytes = 2.0 * ((double)a.R * a.N + (double)a.M * a.N) + (a.bias != nullptr ? 2.0 * a.N : 0.0);
+  if (fused) w.bytes += 2.0 * ((double)a.M * a.K1 + (double)a.K1 * a.R);
+  else w.bytes += (double)a.M * a.R * (a.z_splits == 0 ? 2.0 : 4.0 * a.z_splits);
+  w.bytes += reduce_work(a.tail).bytes;
+  return w;
+}
+
 template <int RT, int BN, bool B2_KC, bool FUSED, bool B1_KC>
 static hipError_t launch_one(const ChainArgs& a, hipStream_t s) {
   const long long grid = (long long)a.tiles_m * a.n_slices;
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   static const std::string name =
       kernel_label("chain_kernel", {lbl(RT), lbl(BN), lbl(B2_KC), lbl(FUSED), lbl(B1_KC)});
-  return launch_kernel(name.c_str(), chain_kernel<RT, BN, B2_KC, FUSED, B1_KC>, dim3((unsigned)grid), dim3(256),
+  return launch_kernel(name.c_str(), chain_work(a, FUSED), chain_kernel<RT, BN, B2_KC, FUSED, B1_KC>, dim3((unsigned)grid), dim3(256),
                        s, a);
 }
 
@@ -646,7 +659,7 @@ static hipError_t launch_small_mb(const ChainArgs& a, hipStream_t s) {
   if (grid <= 0 || grid > 0x7fffffffLL) return hipErrorInvalidValue;
   static const std::string name =
       kernel_label("chain_small_kernel", {lbl(MB), lbl(RT), lbl(B2_KC), lbl(FUSED), lbl(B1_KC)});
-  return launch_kernel(name.c_str(), chain_small_kernel<MB, RT, B2_KC, FUSED, B1_KC>, dim3((unsigned)grid),
+  return launch_kernel(name.c_str(), chain_work(a, FUSED), chain_small_kernel<MB, RT, B2_KC, FUSED, B1_KC>, dim3((unsigned)grid),
                        dim3(256), s, a);
 }
 

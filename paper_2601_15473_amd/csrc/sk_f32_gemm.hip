@@ -156,10 +156,10 @@ static hipError_t launch_one(GemmArgs a, hipStream_t s) {
   note_gemm(a, A_KC, B_KC, 4, 4, true);
   if (bmn == 128) {
     static const std::string name = kernel_label("gemm_f32_kernel", {lbl(2), lbl(A_KC), lbl(B_KC), lbl(COLSUM)});
-    return launch_kernel(name.c_str(), gemm_f32_kernel<2, A_KC, B_KC, COLSUM>, dim3((unsigned)grid), dim3(256), s, a);
+    return launch_kernel(name.c_str(), gemm_work(a, 4, 4, true), gemm_f32_kernel<2, A_KC, B_KC, COLSUM>, dim3((unsigned)grid), dim3(256), s, a);
   }
   static const std::string name = kernel_label("gemm_f32_kernel", {lbl(1), lbl(A_KC), lbl(B_KC), lbl(COLSUM)});
-  return launch_kernel(name.c_str(), gemm_f32_kernel<1, A_KC, B_KC, COLSUM>, dim3((unsigned)grid), dim3(256), s, a);
+  return launch_kernel(name.c_str(), gemm_work(a, 4, 4, true), gemm_f32_kernel<1, A_KC, B_KC, COLSUM>, dim3((unsigned)grid), dim3(256), s, a);
 }
 
 hipError_t launch_gemm_f32(GemmKind kind, const GemmArgs& a, hipStream_t s) {

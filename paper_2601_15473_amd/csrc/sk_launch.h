@@ -20,7 +20,7 @@ struct LaunchHooks {
   virtual void access(const void* p, uint64_t bytes, bool write) = 0;   // of the launch that follows
   virtual void launch_recorded() = 0;
   // profile mode: events around the launch
-  virtual void before(const char* name, unsigned groups, hipStream_t s) = 0;
+  virtual void before(const char* name, unsigned groups, double flops, double bytes, hipStream_t s) = 0;
   virtual void after(hipStream_t s) = 0;
 };
 LaunchHooks* launch_hooks();   // the calling thread's, or null (the normal case)
@@ -38,15 +38,22 @@ inline void note_matrix(const void* p, int64_t rows, int64_t cols, int64_t ld, i
   h->access(p, (uint64_t)(((rows - 1) * ld + cols) * esize), write);
 }
 
+// What a launch is worth to the method, for the per-kernel timing: the flops of the products
+// it forms and the bytes it must move (each operand read once, each result written once --
+// re-reads across tiles and cache traffic are not counted).
+struct Work {
+  double flops, bytes;
+};
+
 template <typename... KArgs>
-inline hipError_t launch_kernel(const char* name, void (*kernel)(KArgs...), dim3 grid, dim3 block,
+inline hipError_t launch_kernel(const char* name, Work work, void (*kernel)(KArgs...), dim3 grid, dim3 block,
                                 hipStream_t s, typename std::common_type<KArgs>::type... args) {
   LaunchHooks* h = launch_hooks();
   if (h != nullptr && h->tracing()) {
     h->launch_recorded();
     return hipSuccess;
   }
-  if (h != nullptr) h->before(name, grid.x * grid.y * grid.z, s);
+  if (h != nullptr) h->before(name, grid.x * grid.y * grid.z, work.flops, work.bytes, s);
   void* ptrs[] = {const_cast<void*>(static_cast<const void*>(&args))...};
   const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, s);
   if (h != nullptr) h->after(s);
@@ -117,6 +124,20 @@ inline void note_gemm(const GemmArgs& a, bool a_kc, bool b_kc, int esize, int os
   note_matrix(a.C, rows, n_store, a.ldc, osize, true);
   if (a.bias != nullptr) note_matrix(a.bias, 1, a.N, a.N, esize, false);
   if (a.colsum != nullptr) note_matrix(a.colsum, a.splits, a.N, a.N, 4, true);
+}
+inline Work gemm_work(const GemmArgs& a, int esize, int osize, bool slabs) {
+  const double n_store = a.n_store > 0 ? a.n_store : a.N;
+  Work w;
+  w.flops = 2.0 * a.M * a.N * a.K;
+  w.bytes = ((double)a.M * a.K + (double)a.K * a.N) * esize + (double)a.M * n_store * osize * (slabs ? a.splits : 1) +
+            (a.bias != nullptr ? (double)a.N * esize : 0.0) + (a.colsum != nullptr ? (double)a.splits * a.N * 4 : 0.0);
+  return w;
+}
+inline Work reduce_work(const ReduceArgs& r) {
+  Work w;
+  w.flops = 0.0;
+  w.bytes = 4.0 * ((double)r.n * (r.n > 0 ? r.splits + 1 : 0) + (double)r.n2 * (r.n2 > 0 ? r.splits2 + 1 : 0));
+  return w;
 }
 inline void note_reduce(const ReduceArgs& r) {
   if (!tracing()) return;

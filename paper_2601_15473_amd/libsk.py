@@ -74,7 +74,8 @@ class TraceAccess(ctypes.Structure):
 
 
 class KernelTime(ctypes.Structure):
-    _fields_ = [("name", ctypes.c_char * 120), ("ms", ctypes.c_float), ("groups", ctypes.c_int32)]
+    _fields_ = [("name", ctypes.c_char * 120), ("ms", ctypes.c_float), ("groups", ctypes.c_int32),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 _lib.sk_set_tuning.restype = ctypes.c_int32
@@ -203,12 +204,13 @@ def sk_profile_begin(max_kernels):
 
 
 def sk_profile_end(max_kernels):
-    """-> list of (kernel name, ms, work-groups), one per launch, in launch order."""
+    """-> list of (kernel name, ms, work-groups, flops, bytes), one per launch, in launch order."""
     buf = (KernelTime * max_kernels)()
     n = _lib.sk_profile_end(buf, max_kernels)
     if n < 0:
         raise RuntimeError(f"sk_profile_end failed ({n})")
-    return [(k.name.decode(), float(k.ms), int(k.groups)) for k in buf[:min(n, max_kernels)]]
+    return [(k.name.decode(), float(k.ms), int(k.groups), float(k.flops), float(k.bytes))
+            for k in buf[:min(n, max_kernels)]]
 
 
 def check(status):

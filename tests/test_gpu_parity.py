@@ -124,7 +124,7 @@ def _kernels_of(sk, dev, calls=("fwd", "bwd_input", "bwd_weight")):
         for c in calls:
             sk.check(getattr(dev, c)())
     finally:
-        names = [n for n, _, _ in sk.sk_profile_end(64)]
+        names = [r[0] for r in sk.sk_profile_end(64)]
     torch.cuda.synchronize()
     return names
 
