@@ -30,6 +30,10 @@ struct GemmTile {
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   static constexpr int STAGE = TA::ELEMS + TB::ELEMS;
   static constexpr int LDS_BYTES = 2 * STAGE * 2;
+  // bf16 results leave through a wave-private strip of LDS (32 rows of the wave's sub-tile at
+  // a time, see the epilogue), carved out of a main buffer that is idle by then.
+  static constexpr int WAVE_STRIP = 32 * WN * 2;
+  static_assert((NTH / 64) * WAVE_STRIP <= STAGE * 2, "the waves' strips fit one main buffer");
   // stride > 0: the work-group goes on to tiles block + stride, block + 2 stride, ... below
   // `total` (large tiles only), fetching the next tile's first chunk behind the last
   // MFMAs of the current one.
@@ -244,25 +248,34 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
     }
   }
 
-  // ---- epilogue: accumulators -> global, straight from registers ----
+  // ---- epilogue: accumulators -> global ----
   // Lane l owns output row l % 32 of each 32-row block and, for q = 0..3, the four
-  // columns 8 q + 4 (l / 32) .. +3 of each 32-column block: 16 bytes of fp32 as they are;
-  // for bf16 the two half-waves exchange the halves of neighbouring column groups
-  // (v_permlane32_swap), after which every lane holds eight consecutive columns.  Either
-  // way a store instruction writes 32-byte row segments, which the L2 merges into lines;
-  // going through LDS to form longer segments cost two barriers per 32-row block.
+  // columns 8 q + 4 (l / 32) .. +3 of each 32-column block.
+  //   fp32: those 16 bytes are stored as they are (32-byte row segments, merged by the L2).
+  //   bf16: the two half-waves exchange the halves of neighbouring column groups
+  //     (v_permlane32_swap), after which every lane holds eight consecutive columns; the
+  //     wave then turns each 32-row block of its sub-tile over through a strip of LDS that
+  //     only it touches (no barrier: one wave's LDS operations execute in order), so that
+  //     eight consecutive lanes hold one whole row of the sub-tile and a store instruction
+  //     writes complete 128-byte lines.  Stored straight from registers the same data left as
+  //     32 scattered 32-byte segments per instruction, which the store path takes four
+  //     times as long to work through: with the stores switched off the [8192 x 512] .
+  //     [512 x 4096] product of BERT-large took 37 us instead of 50, and most of that gap
+  //     stayed when the stores went to a cache-resident scratch target instead, i.e. it was
+  //     the instructions, not the bytes.  Pieces are XOR-swizzled by row so that neither the
+  //     column-wise writes nor the row-wise reads collide on LDS banks.
   OutT* __restrict__ C = static_cast<OutT*>(p.C) +
                          (sizeof(OutT) == 4 ? (int64_t)split * p.M * p.ldc : (int64_t)0);
   const float scale = p.scale;
   const int wn0 = n0 + wn * WN;  // first global column of this wave
   const int n_store = p.n_store > 0 ? p.n_store : p.N;
 
+  if constexpr (sizeof(OutT) == 4) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int gm = m0 + wm * WM + i * 32 + (lane & 31);
+    for (int i = 0; i < TM; ++i) {
+      const int gm = m0 + wm * WM + i * 32 + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      if constexpr (sizeof(OutT) == 4) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int gn = wn0 + j * 32 + q * 8 + (lane >> 5) * 4;
@@ -271,7 +284,22 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
                 make_float4(acc[i][j][q * 4 + 0] * scale, acc[i][j][q * 4 + 1] * scale,
                             acc[i][j][q * 4 + 2] * scale, acc[i][j][q * 4 + 3] * scale);
         }
-      } else {
+    }
+  } else {
+    constexpr int PPRW = WN / 8;        // 16-byte pieces per row of the wave's sub-tile
+    constexpr int RPI = 64 / PPRW;      // rows one store instruction covers
+    constexpr int ROW_BYTES = WN * 2;
+    // The strips live in the main buffer that is idle now.  Large tiles: the one the last
+    // chunk was multiplied out of (everybody passed the barrier behind it; the other buffer
+    // may already hold the first chunk of the work-group's next tile).  Small tiles: their
+    // last k step still read fragments after the loop's last barrier, so one more comes first.
+    if constexpr (PF != 1) __syncthreads();
+    unsigned char* const strip = smem + (PF == 1 ? ((chunk + 1) & 1) * STAGE * 2 : 0) + wave * WAVE_STRIP;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row_w = lane & 31;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
           uint2 w[2];
@@ -292,11 +320,19 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
           typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
           const u32x2 s0 = __builtin_amdgcn_permlane32_swap(w[0].x, w[1].x, false, false);
           const u32x2 s1 = __builtin_amdgcn_permlane32_swap(w[0].y, w[1].y, false, false);
-          const int gn = wn0 + j * 32 + 16 * pr + 8 * (lane >> 5);
-          if (gm < p.M && gn < n_store)
-            *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(C) + (int64_t)gm * p.ldc + gn) =
-                make_uint4(s0.x, s1.x, s0.y, s1.y);
+          // columns j * 32 + 16 pr + 8 (l / 32) .. + 7 of the sub-tile: piece 4 j + 2 pr + l / 32
+          const int piece = j * 4 + pr * 2 + (lane >> 5);
+          *reinterpret_cast<uint4*>(strip + row_w * ROW_BYTES + ((piece ^ (row_w & (PPRW - 1))) * 16)) =
+              make_uint4(s0.x, s1.x, s0.y, s1.y);
         }
+#pragma unroll
+      for (int r0 = 0; r0 < 32; r0 += RPI) {
+        const int row_r = r0 + lane / PPRW, piece = lane % PPRW;
+        const uint4 v = *reinterpret_cast<const uint4*>(strip + row_r * ROW_BYTES + ((piece ^ (row_r & (PPRW - 1))) * 16));
+        const int gm = m0 + wm * WM + i * 32 + row_r;
+        const int gn = wn0 + piece * 8;
+        if (gm < p.M && gn < n_store)
+          *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(C) + (int64_t)gm * p.ldc + gn) = v;
       }
     }
   }
@@ -318,6 +354,8 @@ GemmTile<BM, BN, WAVES_M, WAVES_N, A_KC, B_KC, OutT, COLSUM, PF>::run(const Gemm
   }
 
   if (!has_next) break;
+  // (the next tile's first chunk will store into the buffer the strips were in)
+  if constexpr (sizeof(OutT) == 2) __syncthreads();
   block += stride;
   here = next;
   }  // tiles of this work-group
