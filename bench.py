@@ -3,9 +3,11 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
-One step = forward + input gradient + factor/bias gradient (the three libsk
-entry points) over one batch of synthetic input that is already resident in
-HBM.  Prints ONE JSON line.
+One step = forward (sk_linear_fwd) + input, factor and bias gradients
+(sk_linear_bwd, both gradients in one call) over one batch of synthetic input
+that is already resident in HBM.  Prints ONE JSON line.  The same step through
+the three separate entry points is timed beside it (`three_call_step`), and
+every entry point by itself (`per_call`).
 
 Headline (`value`, `config`, `roofline`, `cpu_baseline`): the largest benchmark
 configuration, c4_llm_mlp, unless --workload names another.  `value` is tokens
@@ -63,9 +65,11 @@ def algorithmic(w, op):
         b = e * (T * (i + o) + R * (i + o))
     elif op == "bwd_weight":
         b = e * (T * (i + o) + i * R) + 4 * (R * o + o)
-    elif op == "bwd":  # both gradients: x and dY in once, dX, dU, db out
+    elif op == "bwd":
+        # both gradients from one call: counted as the two gradient calls it stands for (dY read by
+        # each, as the library does); a single pass over dY would need e * T * out bytes fewer
         flops = 4 * T * R * (i + o)
-        b = e * (T * (2 * i + o) + R * (i + o)) + 4 * (R * o + o)
+        b = e * (T * (i + o) + R * (i + o)) + e * (T * (i + o) + i * R) + 4 * (R * o + o)
     else:  # bwd_weight_first: x, dY and the fixed half of the second stage in, dA out
         h = R // 2
         flops = 2 * T * h * (i + o)
@@ -178,11 +182,13 @@ class Harness:
         n_sets = max(2, min(64, int(np.ceil(2 * INFINITY_CACHE_BYTES / per_set))))
         sets = [one] + [Layer(tensors, sk, poison=False) for _ in range(n_sets - 1)]
 
-        ops = ("fwd", "bwd_input", "bwd_weight")
+        # the step: forward, then both gradients from sk_linear_bwd (one call whose kernels share
+        # launches where that pays); --three-calls times the three separate entry points instead
+        ops = ("fwd", "bwd")
+        if args.three_calls:
+            ops = ("fwd", "bwd_input", "bwd_weight")
         if args.two_sided and headline:
-            ops += ("bwd_weight_first",)
-        if args.single_call_backward and headline:
-            ops = ("fwd", "bwd")
+            ops = ("fwd", "bwd_input", "bwd_weight", "bwd_weight_first")
 
         def step(d):
             for op in ops:
@@ -202,22 +208,24 @@ class Harness:
                "tokens": w.tokens, "in": w.d_in, "out": w.d_out, "l": w.l, "k": w.k, "R": w.R, "dtype": w.dtype,
                "steps_per_batch": steps, "buffer_sets": n_sets, "wall_s_timed_region": wall}
 
-        if ops == ("fwd", "bwd_input", "bwd_weight"):
-            def step_single(d):
-                self.call(d, "fwd")
-                self.call(d, "bwd")
+        if ops == ("fwd", "bwd"):
+            def step_three(d):
+                for op in ("fwd", "bwd_input", "bwd_weight"):
+                    self.call(d, op)
             with torch.cuda.stream(self.stream):
                 for i in range(min(warmup, 5)):
-                    step_single(sets[i % n_sets])
-            ms_single, _ = self.batches(lambda i: step_single(sets[i % n_sets]), steps)
-            res["single_call_backward_ms_per_step"] = ms_single
+                    step_three(sets[i % n_sets])
+            ms_three, _ = self.batches(lambda i: step_three(sets[i % n_sets]), steps)
+            res["three_call_ms_per_step"] = ms_three
 
         per_op, flops_step, bytes_step = {}, 0, 0
-        for op in ops:
+        timed_ops = ops if (args.two_sided and headline) else ("fwd", "bwd", "bwd_input", "bwd_weight")
+        for op in timed_ops:
             ms, _ = self.batches(lambda i, op=op: self.call(sets[i % n_sets], op), steps)
             f, b = algorithmic(w, op)
-            flops_step += f
-            bytes_step += b
+            if op in ops:
+                flops_step += f
+                bytes_step += b
             per_op[op] = {"ms": ms, "tflops": f / ms / 1e9, "gbs": b / ms / 1e6}
         peak_tf = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
         t_mfma = flops_step / (peak_tf * 1e12)
@@ -227,7 +235,7 @@ class Harness:
                    tflops=flops_step / (ms_step * 1e-3) / 1e12, gbs=bytes_step / (ms_step * 1e-3) / 1e9,
                    tokens_per_s=w.tokens / (ms_step * 1e-3),
                    algorithmic_flops_per_step=flops_step, algorithmic_bytes_per_step=bytes_step)
-        for op in ops:
+        for op in timed_ops:
             f, b = algorithmic(w, op)
             per_op[op]["frac"] = max(f / (peak_tf * 1e12), b / (HBM_PEAK_GBS * 1e9)) / (per_op[op]["ms"] * 1e-3)
 
@@ -356,8 +364,9 @@ def main():
     ap.add_argument("--no-measured-peak", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--tokens", type=int, default=0, help="override the headline workload's token count")
-    ap.add_argument("--single-call-backward", action="store_true",
-                    help="one step = sk_linear_fwd + sk_linear_bwd (both gradients in one call)")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="one step = sk_linear_fwd + sk_linear_bwd_input + sk_linear_bwd_weight instead of "
+                         "sk_linear_fwd + sk_linear_bwd (both gradients in one call)")
     ap.add_argument("--two-sided", action="store_true",
                     help="the two-sided reading of the layer: half of the workload's terms on each "
                          "side (same stage-matrix shapes), four calls per step")
@@ -375,8 +384,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
-    if args.single_call_backward and args.two_sided:
-        sys.exit("bench.py: --single-call-backward and --two-sided do not combine")
+    if args.three_calls and args.two_sided:
+        sys.exit("bench.py: --two-sided already times the separate calls (four per step)")
     w = W.BY_NAME[args.workload]
     if args.tokens:
         w = W.scaled(w, tokens=args.tokens)
@@ -434,11 +443,12 @@ def main():
         "roofline": roofline,
         "kernels": head["kernels"],
     }
-    if "single_call_backward_ms_per_step" in head:
-        out["single_call_backward"] = {
-            "what": "the same step as sk_linear_fwd + sk_linear_bwd (both gradients in one call); not used for `value`",
-            "ms_per_step": head["single_call_backward_ms_per_step"],
-            "tokens_per_s": w.tokens / (head["single_call_backward_ms_per_step"] * 1e-3)}
+    if "three_call_ms_per_step" in head:
+        out["three_call_step"] = {
+            "what": "the same step as sk_linear_fwd + sk_linear_bwd_input + sk_linear_bwd_weight (three entry points, "
+                    "dY read by both gradient calls); not used for `value`",
+            "ms_per_step": head["three_call_ms_per_step"],
+            "tokens_per_s": w.tokens / (head["three_call_ms_per_step"] * 1e-3)}
     if "dense_context" in head:
         out["dense_context"] = head["dense_context"]
 
@@ -463,7 +473,7 @@ def main():
     if not args.no_configs:
         cfgs = {}
         for cw in (W.BERT_BASE_FFN_UP,) + W.BERT_BASE_PROJ + (W.BERT_LARGE_FFN_UP, W.BERT_LARGE_FFN_DOWN, W.LLM_MLP):
-            if cw.name == w.name and not args.tokens and not args.two_sided and not args.single_call_backward:
+            if cw.name == w.name and not args.tokens and not args.two_sided:
                 continue   # the headline itself
             big = cw.tokens * cw.R * (cw.d_in + cw.d_out) > 1e12
             r, _, _ = h.measure(cw, 20 if big else 200, 5 if big else 20, headline=False)
