@@ -370,6 +370,8 @@ def main():
     ap.add_argument("--two-sided", action="store_true",
                     help="the two-sided reading of the layer: half of the workload's terms on each "
                          "side (same stage-matrix shapes), four calls per step")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
+                    help="force a plan parameter (sk_set_tuning), e.g. narrow_bwd=0; for sweeps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -392,6 +394,9 @@ def main():
     if args.two_sided and w.l % 2:
         sys.exit("bench.py: --two-sided needs an even number of terms to split over the two sides")
     sk.sk_set_plan(args.plan)
+    for kv in args.tune:
+        knob, _, value = kv.partition("=")
+        sk.sk_set_tuning(getattr(sk, "SK_TUNE_" + knob.upper()), int(value))
     h = Harness(torch, sk, W, dm, args)
 
     head, tensors, ops = h.measure(w, args.steps, args.warmup, headline=True)

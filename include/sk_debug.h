@@ -30,7 +30,9 @@ typedef enum {
   SK_TUNE_SLICES = 4,   /* output slices per token tile in the chain kernels */
   SK_TUNE_STILE = 5,    /* tile of the split first contraction of the split+expand plan */
   SK_TUNE_SSPLITS = 6,  /* number of splits of that contraction */
-  SK_TUNE_COUNT = 7
+  SK_TUNE_NARROW_BWD = 7, /* sk_linear_bwd's one-pass schedule for narrow sketches: 0 = never, 1 = wherever
+                           the kernel can serve the shape */
+  SK_TUNE_COUNT = 8
 } sk_tune_knob;
 
 /* Returns the previous value (negative = automatic), or INT32_MIN for an unknown knob. */

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "lib", "libsk.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["sk_api.hip", "sk_bf16_gemm.hip", "sk_f32_gemm.hip", "sk_chain.hip"]
+SOURCES = ["sk_api.hip", "sk_bf16_gemm.hip", "sk_f32_gemm.hip", "sk_chain.hip", "sk_bwd_narrow.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed fp32 VALU forms are kept off on the test machines

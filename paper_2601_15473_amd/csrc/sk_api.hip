@@ -28,7 +28,7 @@ thread_local std::string g_hip_error;
 std::atomic<int> g_plan{0};
 
 // Forced plan parameters (sk_set_tuning; negative = the planner chooses).
-std::atomic<int> g_tune[SK_TUNE_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+std::atomic<int> g_tune[SK_TUNE_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 int tune(sk_tune_knob knob) { return g_tune[knob].load(std::memory_order_relaxed); }
 
 // The calling thread's launch trace or kernel timer (include/sk_debug.h); null otherwise.
@@ -478,6 +478,39 @@ size_t first_stage_bytes(const Shape& s, int64_t nc) {
   return align_up((size_t)s.T * nc * s.esize) + (da_slabs > g_slabs ? da_slabs : g_slabs);
 }
 
+// Both gradients of a narrow sketch in one pass over x and dY (sk_bwd_narrow.hip): a
+// work-group per 64-token tile produces its rows of dX outright and leaves one fp32 slab of
+// dU_cat (and of dbias) behind, which a second kernel sums; G never leaves the chip and
+// three launches become two.  What it costs: every work-group fetches all of S_cat and
+// U_cat and writes a whole slab (R x out floats) whatever its share of the tokens, so a CU
+// moves about 2.5 times the bytes of its x, dY and dX tiles, and a CU sustains only some
+// 40-50 GB/s.  Measured on MI355X (in = out = 768, backward call): R = 32 -- 28.5 against
+// 23.3 us for the three-launch schedule at 4096 tokens (64 work-groups: a quarter of the
+// chip), 31.1 against 30.6 at 8192, 36.4 against 38.7 at 16384; R = 64 (a variant of the
+// kernel since removed) lost at every size.  So: R <= 32, a token tile for at least three
+// quarters of the CUs, and slabs of at most 32 MiB.
+struct NarrowPlan {
+  bool ok;
+  int tiles_m;
+  size_t du_bytes, db_bytes;
+  size_t total() const { return du_bytes + db_bytes; }
+};
+
+NarrowPlan plan_narrow(const Shape& s) {
+  NarrowPlan n{};
+  const int forced = tune(SK_TUNE_NARROW_BWD);
+  if (s.dtype != SK_BF16 || g_plan.load(std::memory_order_relaxed) != PLAN_AUTO || forced == 0) return n;
+  if (s.in > narrow_bwd_max_in(s.R)) return n;   // (0 for a sketch the kernel does not serve)
+  const int64_t tiles_m = (s.T + 63) / 64;
+  const size_t du = (size_t)tiles_m * s.R * s.out * 4;
+  if (forced < 0 && (du > ((size_t)32 << 20) || tiles_m < 3 * NUM_CUS / 4)) return n;
+  n.ok = true;
+  n.tiles_m = (int)tiles_m;
+  n.du_bytes = align_up(du);
+  n.db_bytes = align_up((size_t)tiles_m * s.out * 4);
+  return n;
+}
+
 size_t workspace_for(sk_op op, const Shape& s) {
   const size_t mid = align_up((size_t)s.T * s.R * s.esize);  // Z or G
   switch (op) {
@@ -499,8 +532,11 @@ size_t workspace_for(sk_op op, const Shape& s) {
     }
     case SK_OP_BWD_WEIGHT:
       return plan_weight(s).total();
-    case SK_OP_BWD:
-      return workspace_for(SK_OP_BWD_INPUT, s) + workspace_for(SK_OP_BWD_WEIGHT, s);
+    case SK_OP_BWD: {
+      const size_t two = workspace_for(SK_OP_BWD_INPUT, s) + workspace_for(SK_OP_BWD_WEIGHT, s);
+      const NarrowPlan n = plan_narrow(s);
+      return n.ok && n.total() > two ? n.total() : two;
+    }
     case SK_OP_BWD_WEIGHT_FIRST: {
       // the maximum over every admissible column count (narrow ranges split the tokens
       // further), so one buffer serves any range
@@ -899,9 +935,28 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
   if (st != SK_OK) return st;
   const size_t in_bytes = workspace_for(SK_OP_BWD_INPUT, s);
   const size_t w_bytes = workspace_for(SK_OP_BWD_WEIGHT, s);
-  if (!workspace || workspace_bytes < in_bytes + w_bytes) return SK_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < workspace_for(SK_OP_BWD, s)) return SK_ERR_WORKSPACE;
   unsigned char* ws_in = static_cast<unsigned char*>(workspace);
   unsigned char* ws_w = ws_in + in_bytes;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const float scale = 1.0f / (float)l;
+
+  // --- narrow sketch, short input: one pass over x and dY | sum of the token tiles' slabs ---
+  if (const NarrowPlan n = plan_narrow(s); n.ok) {
+    g_hip_error.clear();
+    NarrowBwdArgs b{};
+    b.x = x; b.S = S_cat; b.dY = dY; b.U = U_cat; b.dX = dX;
+    b.du_slabs = reinterpret_cast<float*>(ws_in);
+    b.db_slabs = dbias ? reinterpret_cast<float*>(ws_in + n.du_bytes) : nullptr;
+    b.M = (int)tokens; b.K1 = (int)in; b.R = s.R; b.N = (int)out; b.scale = scale;
+    hipError_t e = launch_bwd_narrow_bf16(b, hs);
+    if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (one pass over x and dY)");
+    ReduceArgs t{};
+    t.part = b.du_slabs; t.out = dU_cat; t.n = (int64_t)s.R * out; t.splits = n.tiles_m; t.scale = scale;
+    t.part2 = b.db_slabs; t.out2 = dbias; t.n2 = dbias ? out : 0; t.splits2 = n.tiles_m; t.scale2 = 1.0f;
+    e = launch_reduce_tiles(t, hs);
+    return e == hipSuccess ? SK_OK : hip_fail(e, "sk_linear_bwd (sum of the token tiles)");
+  }
 
   // Shared-launch schedules exist for the shapes the automatic plans produce on the
   // benchmark configurations (bf16; the dual kernel is built for a few tile pairs only);
@@ -913,8 +968,6 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
   const Plan in_plan = pick_plan(s, SK_OP_BWD_INPUT);
   const int z_tile = bf16_auto ? choose_tile(s.R, tokens, in, 1) : -1;
   const GemmKind du_kind = GEMM_NN_F32_COLSUM;
-  hipStream_t hs = static_cast<hipStream_t>(stream);
-  const float scale = 1.0f / (float)l;
 
   void* Z = ws_w;
   float* part = reinterpret_cast<float*>(ws_w + w.z_bytes);

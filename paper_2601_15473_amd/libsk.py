@@ -65,7 +65,8 @@ _lib.sk_set_plan.restype = ctypes.c_int
 _lib.sk_set_plan.argtypes = [ctypes.c_int]
 
 # ---- testing / tuning / measurement aids (include/sk_debug.h) ----
-SK_TUNE_TILE, SK_TUNE_WTILE, SK_TUNE_WSPLITS, SK_TUNE_BM, SK_TUNE_SLICES, SK_TUNE_STILE, SK_TUNE_SSPLITS = range(7)
+(SK_TUNE_TILE, SK_TUNE_WTILE, SK_TUNE_WSPLITS, SK_TUNE_BM, SK_TUNE_SLICES, SK_TUNE_STILE, SK_TUNE_SSPLITS,
+ SK_TUNE_NARROW_BWD) = range(8)
 
 
 class TraceAccess(ctypes.Structure):

@@ -126,7 +126,7 @@ def test_single_call_backward_argument_checks_and_workspace():
         both = sk.sk_linear_workspace_bytes(sk.SK_OP_BWD, *a)
         parts = (sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_INPUT, *a) +
                  sk.sk_linear_workspace_bytes(sk.SK_OP_BWD_WEIGHT, *a))
-        assert both == parts            # the two gradients' buffers side by side
+        assert both >= parts            # room for the two gradients' buffers side by side
         assert f(P, P, P, P, P, P, None, *a, P, both - 1) == sk.SK_ERR_WORKSPACE
 
 

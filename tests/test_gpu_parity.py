@@ -268,15 +268,68 @@ def test_single_call_backward(sk, w):
     sk.check(sep.bwd_input())
     sk.check(sep.bwd_weight())
     torch.cuda.synchronize()
-    assert torch.equal(dev.dU.view(torch.int32), sep.dU.view(torch.int32))
-    assert torch.equal(dev.db.view(torch.int32), sep.db.view(torch.int32))
+    one_pass = any("bwd_narrow" in n for n in _kernels_of(sk, DeviceLayer(t, sk), ("bwd",)))
+    if one_pass:   # per-token-tile partial sums: another summation order than the separate call's
+        assert rel_err(to_f64(dev.dU), to_f64(sep.dU)) <= TOL[w.dtype]
+        assert rel_err(to_f64(dev.db), to_f64(sep.db)) <= TOL[w.dtype]
+    else:
+        assert torch.equal(dev.dU.view(torch.int32), sep.dU.view(torch.int32))
+        assert torch.equal(dev.db.view(torch.int32), sep.db.view(torch.int32))
     assert rel_err(to_f64(dev.dX), to_f64(sep.dX)) <= TOL[w.dtype]
     # no bias gradient wanted
     nob = DeviceLayer(t, sk)
     sk.check(nob.bwd(with_db=False))
     torch.cuda.synchronize()
     assert torch.isnan(nob.db).all()
-    assert torch.equal(nob.dU.view(torch.int32), sep.dU.view(torch.int32))
+    assert torch.equal(nob.dU.view(torch.int32), dev.dU.view(torch.int32))
+
+
+NARROW_CASES = [
+    # (workload, forced): the one-pass schedule where the planner takes it by itself (many
+    # token tiles) and forced onto small cases: ragged token tiles, a single chunk, chunk
+    # counts on both sides of a pass of eight (out = 1024 | 1040 | 2320), R below the kernel's
+    # width, the longest input it takes
+    (W.scaled(W.BERT_BASE_PROJ[0], tokens=16384), False),
+    (W.Workload("narrow_many_tiles", 20000, 96, 160, 1, 32, "bf16", seed=36), False),
+    (W.scaled(W.BERT_BASE_PROJ[0], tokens=1237), True),
+    (W.Workload("narrow_r16", 3333, 144, 336, 1, 16, "bf16", seed=37), True),
+    (W.Workload("narrow_one_chunk", 130, 64, 48, 1, 16, "bf16", seed=32), True),
+    (W.Workload("narrow_longest_in", 200, 848, 208, 2, 16, "bf16", seed=33), True),
+    (W.Workload("narrow_full_pass", 77, 400, 1024, 1, 32, "bf16", seed=34), True),
+    (W.Workload("narrow_pass_and_a_bit", 150, 112, 1040, 1, 32, "bf16", seed=38), True),
+    (W.Workload("narrow_three_passes", 100, 64, 2320, 2, 16, "bf16", seed=39), True),
+    (W.Workload("narrow_one_token", 1, 16, 16, 1, 16, "bf16", seed=35), True),
+]
+
+
+@pytest.mark.parametrize("w,forced", NARROW_CASES, ids=lambda v: v.name if hasattr(v, "name") else ("forced" if v else "auto"))
+def test_one_pass_backward_for_narrow_sketches(sk, tuning, w, forced):
+    """sk_linear_bwd's one-pass schedule (a kernel that reads x and dY once, writes dX and
+    leaves a slab of dU and db per token tile, then the sum of the slabs): the kernel runs --
+    by the planner's own choice on the large cases, forced on the small ones -- and every
+    element of dX, dU and db agrees with the oracle."""
+    print(f"case narrow {w.name} T={w.tokens} in={w.d_in} out={w.d_out} l={w.l} k={w.k} forced={forced}", flush=True)
+    sk.sk_set_plan(0)
+    if forced:
+        tuning(sk.SK_TUNE_NARROW_BWD, 1)
+    t = W.generate(w)
+    names = _kernels_of(sk, DeviceLayer(t, sk), ("bwd",))
+    assert len(names) == 2 and "bwd_narrow_kernel" in names[0] and "reduce_tiles" in names[1], names
+    dev = DeviceLayer(t, sk)
+    sk.check(dev.bwd())
+    torch.cuda.synchronize()
+    want = oracle_all(t)
+    got = dict(dX=to_f64(dev.dX), dU=to_f64(dev.dU), db=to_f64(dev.db))
+    errs = {n: rel_err(got[n], want[n]) for n in got}
+    print("   errors:", {n: f"{e:.2e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= TOL[w.dtype], (n, e)
+    again = DeviceLayer(t, sk)
+    sk.check(again.bwd())
+    torch.cuda.synchronize()
+    for a, b in ((dev.dX, again.dX), (dev.dU, again.dU), (dev.db, again.db)):   # bit-reproducible
+        assert torch.equal(a.view(torch.int16 if a.element_size() == 2 else torch.int32),
+                           b.view(torch.int16 if b.element_size() == 2 else torch.int32))
 
 
 def _random_shapes(n, seed):

@@ -125,6 +125,8 @@ def _forced(r):
             out.append((knob, int(r.integers(lo, hi))))
     if r.random() < 0.3:
         out.append((sk.SK_TUNE_BM, int(r.choice([64, 128]))))
+    if r.random() < 0.3:
+        out.append((sk.SK_TUNE_NARROW_BWD, int(r.integers(0, 2))))
     return tuple(out)
 
 
@@ -151,6 +153,51 @@ def test_benchmark_and_extreme_shapes_every_plan_and_tile(shape):
             _run_shape(r, shape, plan, ((sk.SK_TUNE_TILE, tile), (sk.SK_TUNE_WTILE, tile)))
         for bm in (64, 128):
             _run_shape(r, shape, plan, ((sk.SK_TUNE_BM, bm), (sk.SK_TUNE_SLICES, 3)))
+
+
+def test_one_pass_backward_stays_inside_the_buffers():
+    """sk_linear_bwd's one-pass schedule for narrow sketches (two launches: the pass, then the
+    sum of the token tiles' slabs), chosen by the planner on the first shape and forced on
+    the others: ragged tokens, one chunk, several flush passes, the longest input."""
+    r = np.random.default_rng(11)
+    shapes = [(16384, 768, 768, 2, 16, sk.SK_BF16), (20000, 96, 160, 1, 32, sk.SK_BF16),
+              (1237, 768, 768, 2, 16, sk.SK_BF16), (130, 64, 48, 1, 16, sk.SK_BF16),
+              (200, 848, 208, 2, 16, sk.SK_BF16), (100, 64, 2320, 2, 16, sk.SK_BF16),
+              (1, 16, 16, 1, 16, sk.SK_BF16), (70000, 848, 4096, 1, 32, sk.SK_BF16)]
+    for i, shape in enumerate(shapes):
+        forced = () if i < 2 else ((sk.SK_TUNE_NARROW_BWD, 1),)
+        for knob, value in forced:
+            sk.sk_set_tuning(knob, value)
+        try:
+            B = Buffers(*shape, 16).base
+            sk.sk_trace_begin()
+            try:
+                st = sk.sk_linear_bwd(B["x"], B["dY"], B["S"], B["U"], B["dX"], B["dU"], B["db"], *shape,
+                                      B["ws"], sk.sk_linear_workspace_bytes(sk.SK_OP_BWD, *shape))
+            finally:
+                _, launches = sk.sk_trace_end()
+            assert st == sk.SK_OK and launches == 2, (shape, st, launches)
+        finally:
+            for knob, _ in forced:
+                sk.sk_set_tuning(knob, -1)
+        _run_shape(r, shape, 0, forced)
+    # not taken for wider sketches, longer inputs or other plans
+    for shape, plan in (((16384, 768, 768, 1, 64, sk.SK_BF16), 0), ((16384, 864, 768, 1, 32, sk.SK_BF16), 0),
+                        ((16384, 768, 768, 1, 32, sk.SK_F32), 0), ((16384, 768, 768, 1, 32, sk.SK_BF16), 2)):
+        sk.sk_set_plan(plan)
+        sk.sk_set_tuning(sk.SK_TUNE_NARROW_BWD, 1)
+        try:
+            B = Buffers(*shape, 16).base
+            sk.sk_trace_begin()
+            try:
+                st = sk.sk_linear_bwd(B["x"], B["dY"], B["S"], B["U"], B["dX"], B["dU"], B["db"], *shape,
+                                      B["ws"], sk.sk_linear_workspace_bytes(sk.SK_OP_BWD, *shape))
+            finally:
+                _, launches = sk.sk_trace_end()
+            assert st == sk.SK_OK and launches > 2, (shape, plan, launches)
+        finally:
+            sk.sk_set_tuning(sk.SK_TUNE_NARROW_BWD, -1)
+            sk.sk_set_plan(0)
 
 
 def test_trace_mode_launches_nothing_and_ends_cleanly():
