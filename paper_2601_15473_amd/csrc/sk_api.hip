@@ -481,14 +481,14 @@ size_t first_stage_bytes(const Shape& s, int64_t nc) {
 // Both gradients of a narrow sketch in one pass over x and dY (sk_bwd_narrow.hip): a
 // work-group per 64-token tile produces its rows of dX outright and leaves one fp32 slab of
 // dU_cat (and of dbias) behind, which a second kernel sums; G never leaves the chip and
-// three launches become two.  What it costs: every work-group fetches all of S_cat and
-// U_cat and writes a whole slab (R x out floats) whatever its share of the tokens, so a CU
-// moves about 2.5 times the bytes of its x, dY and dX tiles, and a CU sustains only some
-// 40-50 GB/s.  Measured on MI355X (in = out = 768, backward call): R = 32 -- 28.5 against
-// 23.3 us for the three-launch schedule at 4096 tokens (64 work-groups: a quarter of the
-// chip), 31.1 against 30.6 at 8192, 36.4 against 38.7 at 16384; R = 64 (a variant of the
-// kernel since removed) lost at every size.  So: R <= 32, a token tile for at least three
-// quarters of the CUs, and slabs of at most 32 MiB.
+// three launches become two.  A work-group is four waves on a CU of its own, so nothing
+// hides its latencies but its own prefetching, and it takes about 16 us for its tile
+// whatever the token count; the launch pays when its one round of work-groups covers at
+// least half of the chip.  Measured on MI355X (in = out = 768, R = 32, backward call, one
+// pass against the three-launch schedule): 4096 tokens 24.5 / 22.9 us, 8192 27.2 / 30.7,
+// 12288 30.4 / 35.4, 16384 33.9 / 39.1, 20480 (a second, quarter-full round) 52.9 / 44.5;
+// R = 64 (a variant of the kernel since removed) lost at every size.  So: R <= 32, between
+// half a round and one round of token tiles, slabs of at most 32 MiB.
 struct NarrowPlan {
   bool ok;
   int tiles_m;
@@ -503,7 +503,7 @@ NarrowPlan plan_narrow(const Shape& s) {
   if (s.in > narrow_bwd_max_in(s.R)) return n;   // (0 for a sketch the kernel does not serve)
   const int64_t tiles_m = (s.T + 63) / 64;
   const size_t du = (size_t)tiles_m * s.R * s.out * 4;
-  if (forced < 0 && (du > ((size_t)32 << 20) || tiles_m < 3 * NUM_CUS / 4)) return n;
+  if (forced < 0 && (du > ((size_t)32 << 20) || tiles_m < NUM_CUS / 2 || tiles_m > NUM_CUS)) return n;
   n.ok = true;
   n.tiles_m = (int)tiles_m;
   n.du_bytes = align_up(du);

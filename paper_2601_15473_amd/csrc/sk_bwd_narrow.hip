@@ -6,10 +6,12 @@
 // dU_cat per token tile behind.  For a narrow sketch over a layer of moderate width that
 // partial sum is small, and this kernel does it: a work-group owns 64 tokens and
 //   1. recomputes its Z tile = x_tile . S_cat (64 x R; never read from a saved copy):
-//      S_cat sits in LDS whole, the four waves split the contraction four ways and take
-//      their x fragments straight from global memory (a lane's MFMA fragment is 16
-//      contiguous bytes of an x row), so this stage has no barrier and no LDS traffic for
-//      x; the four partial tiles meet in LDS and are rounded to bf16 once;
+//      S_cat sits in LDS whole and the four waves split the contraction four ways.  A wave
+//      loads its quarter of the x tile as whole 128-byte row segments and turns them into
+//      MFMA fragments through an LDS strip of its own, so this stage needs no barrier
+//      (fragments fetched straight from global memory -- 16 contiguous bytes per lane, but
+//      32 different rows per instruction -- issued four times slower); the four partial
+//      tiles meet in LDS and are rounded to bf16 once;
 //   2. walks its rows of dY in 128-column chunks, each loaded once and stored in LDS in two
 //      layouts (k-contiguous for the product over columns, as it is for the product over
 //      tokens), and from every chunk forms
@@ -23,8 +25,9 @@
 //   3. rounds G to bf16 and expands dX_tile = scale . G . S_cat^T, the S_cat fragments again
 //      straight from global memory (rows of S_cat are k-contiguous for this product).
 // Every wave does the same work in every stage (no divergent roles), every load that does
-// not depend on an earlier stage is issued before the first wait, and results leave through
-// wave-private LDS strips as whole 128-byte lines.  A second, small kernel sums the token
+// not depend on an earlier stage is issued before the first wait, the LDS reads of a step
+// are issued together ahead of its MFMAs, and results leave through wave-private LDS strips
+// as whole 128-byte lines.  A second, small kernel sums the token
 // tiles' slabs into dU_cat and dbias in a fixed order, so results are bit-reproducible.
 #include "sk_bf16_tile.h"
 #include "sk_launch.h"
@@ -42,6 +45,7 @@ struct NarrowLds {
   static constexpr int MAX_IN = S_CAP / (2 * S_LD) / 16 * 16;
   static constexpr int S_PIECES = (MAX_IN * (RT / 8) + 255) / 256;   // 16-byte pieces of S_cat per thread
   static constexpr int X_STEPS = ((MAX_IN / 16) + 3) / 4;            // k steps of stage 1 per wave
+  static constexpr int X_SUBS = (X_STEPS + 3) / 4;                   // 64-wide sub-tiles of x per wave
   static constexpr int DX_GROUPS = ((MAX_IN + 63) / 64 + 3) / 4;     // 64-column groups of dX per wave
   static constexpr int Z_LD = S_LD;
   static constexpr int G_LD = RT + 8;       // G tile, [tokens][R] row-major (read_frag_rowmajor's padding)
@@ -51,19 +55,20 @@ struct NarrowLds {
   static constexpr int CHUNK_BYTES = (TDK::ELEMS + TDN::ELEMS + TU::ELEMS) * 2;
   static constexpr int PASS = 8;            // chunks between flushes: PASS x 16 accumulators
   static constexpr int NSET = 4;            // chunks in flight (register sets); divides PASS
-  // LDS map: Z tile | column sums of a pass | a 4 KB strip per wave for the dU flush | work.
+  // LDS map: Z tile | column sums of a pass | an 8 KB strip per wave (x sub-tiles, then the dU
+  // flush, then dX) | work.
   // work: S_cat (stages 0-1); then two chunk buffers, the partial Z tiles on top of the
   // second one (dead before it is first filled); at the end G and the dX strips.
   static constexpr int Z_BYTES = 64 * Z_LD * 2;
   static constexpr int DB_BYTES = PASS * CW * 4;
-  static constexpr int STRIP_BYTES = 4 * 4096;
+  static constexpr int STRIP_BYTES = 4 * 8192;
   static constexpr int ZPART_OFF = CHUNK_BYTES;
   static constexpr int ZPART_BYTES = 4 * 64 * RT * 4;
   static constexpr int AFTER_S = ZPART_OFF + (ZPART_BYTES > CHUNK_BYTES ? ZPART_BYTES : CHUNK_BYTES);
   static constexpr int WORK_BYTES = S_CAP > AFTER_S ? S_CAP : AFTER_S;
   static constexpr int BYTES = Z_BYTES + DB_BYTES + STRIP_BYTES + WORK_BYTES;
   static_assert(BYTES <= 160 * 1024, "over the LDS of a compute unit");
-  static_assert(16384 + 64 * G_LD * 2 + 4 * 8192 <= WORK_BYTES, "stage 3: G partials, G tile, dX strips");
+  static_assert(16384 + 64 * G_LD * 2 <= WORK_BYTES, "stage 3: G partials, G tile");
   static_assert(PASS % NSET == 0 && NSET % 2 == 0, "register sets and LDS buffers rotate with the pass");
 };
 
@@ -90,7 +95,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   bf16* const Ss = reinterpret_cast<bf16*>(work);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  unsigned char* const ustrip = smem + L::Z_BYTES + L::DB_BYTES + wave * 4096;   // [32 rows][128 bytes]
+  unsigned char* const strip = smem + L::Z_BYTES + L::DB_BYTES + wave * 8192;   // this wave's own
   const int tile_m = blockIdx.x;
   const int m0 = tile_m * 64;
 
@@ -112,21 +117,22 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     const int k = q / PPR, c = (q % PPR) * 8;
     sv[u] = window_load16(sw, (q < s_pieces && c < p.R) ? (unsigned)(k * p.R + c) * 2u : OOB_OFFSET);
   }
-  // this wave's quarter of the x tile, as MFMA fragments
+  // this wave's quarter of the x tile: 64-wide sub-tiles, whole row segments
   const int steps = p.K1 / 16;
   const int per_wave = (steps + 3) / 4;
   const int s_begin = wave * per_wave;
   const int s_end = (s_begin + per_wave < steps) ? s_begin + per_wave : steps;
-  uint4 xa[L::X_STEPS][2];
+  uint4 xv[L::X_SUBS][8];
   {
     const GWindow xw = make_window(X, (int64_t)m0 * p.K1, (int64_t)p.M * p.K1, 2);
 #pragma unroll
-    for (int b = 0; b < L::X_STEPS; ++b)
+    for (int t = 0; t < L::X_SUBS; ++t)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int ks = s_begin + b;
-        const unsigned off = (unsigned)((i * 32 + (lane & 31)) * p.K1 + ks * 16 + (lane >> 5) * 8) * 2u;
-        xa[b][i] = window_load16(xw, ks < s_end ? off : OOB_OFFSET);   // rows past M fall outside the window
+      for (int u = 0; u < 8; ++u) {
+        const int q = u * 64 + lane;
+        const int row = q >> 3, k = (s_begin + t * 4) * 16 + (q & 7) * 8;
+        // (rows past M fall outside the window by themselves)
+        xv[t][u] = window_load16(xw, k < s_end * 16 ? (unsigned)(row * p.K1 + k) * 2u : OOB_OFFSET);
       }
   }
   // the first chunks of dY and U_cat
@@ -155,14 +161,32 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) accz[i][r] = 0.f;
+    bf16* const xt = reinterpret_cast<bf16*>(strip);   // [64 rows][64 k], pieces swizzled by row
 #pragma unroll
-    for (int b = 0; b < L::X_STEPS; ++b) {
-      // (past the wave's range the x fragments are zero; any valid k step serves for S_cat)
-      const int ks = s_begin + b < s_end ? s_begin + b : 0;
-      const bf16x8 fb = read_frag<false, L::S_LD>(Ss, 0, ks, lane);
+    for (int t = 0; t < L::X_SUBS; ++t) {
+      if (s_begin + t * 4 >= s_end) break;   // (the loops are sized for the longest input)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        accz[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, __builtin_bit_cast(bf16x8, xa[b][i]), accz[i], 0, 0, 0);
+      for (int u = 0; u < 8; ++u) {
+        const int q = u * 64 + lane;
+        const int row = q >> 3;
+        *reinterpret_cast<uint4*>(xt + row * 64 + kc_piece<64>(row, q & 7) * 8) = xv[t][u];
+      }
+      bf16x8 fx[4][2], fb[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        // (past the wave's range the x fragments are zero; any valid k step serves for S_cat)
+        const int kg = s_begin + t * 4 + ks < s_end ? s_begin + t * 4 + ks : 0;
+        fb[ks] = read_frag<false, L::S_LD>(Ss, 0, kg, lane);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) fx[ks][i] = read_frag<true, 64>(xt, i * 32, ks, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          accz[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fx[ks][i], accz[i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();   // everybody is done with S_cat: part of its region now takes the partial tiles
     float* const Zpart = reinterpret_cast<float*>(work + L::ZPART_OFF);
@@ -192,6 +216,10 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
       *reinterpret_cast<uint2*>(Zs + row * L::Z_LD + c) = o;
     }
   }
+  __syncthreads();   // Z tile complete
+  bf16x8 fz[4];      // its fragments (rows r, k = tokens) serve every chunk
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) fz[ks] = read_frag<false, L::Z_LD>(Zs, 0, ks, lane);
 
   // ---------------- stage 2: the rows of dY, one 128-column chunk at a time ----------------
   auto store_chunk = [&](int buf, const uint4 (&d)[TDK::PIECES], const uint4 (&u)[TU::PIECES]) {
@@ -225,33 +253,38 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     // LDS buffers alternate; a register set is reloaded as soon as it has been stored, so
     // NSET - 1 chunks are in flight behind the one being multiplied.  One barrier per chunk:
     // a wave that stores into a buffer has passed the barrier that every wave reaches only
-    // after its last read of that buffer.  (The very first barrier also publishes the Z tile.)
+    // after its last read of that buffer.
     static_for<0, PASS>([&](auto cpc) {
       constexpr int cp = cpc.value, set = cp % NSET, buf = cp & 1;
+      if (c0 + cp >= n_chunks) return;   // (uniform over the work-group)
       store_chunk(buf, rd[set], ru[set]);
-      load_chunk(rd[set], ru[set], c0 + cp + NSET);   // (past the last chunk: zeros)
+      load_chunk(rd[set], ru[set], c0 + cp + NSET);   // (past the last chunk: every lane masked)
       __syncthreads();
       const bf16* dk = reinterpret_cast<const bf16*>(work + buf * L::CHUNK_BYTES);
       const bf16* dn = dk + TDK::ELEMS;
       const bf16* uk = dn + TDN::ELEMS;
+      bf16x8 fa[GK], fb[GK], fd[4];
 #pragma unroll
       for (int ks = 0; ks < GK; ++ks) {
-        const bf16x8 fa = read_frag<true, TDK::LD>(dk, gi * 32, gk0 + ks, lane);
-        const bf16x8 fb = read_frag<true, TU::LD>(uk, 0, gk0 + ks, lane);
-        accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, accg, 0, 0, 0);
+        fa[ks] = read_frag<true, TDK::LD>(dk, gi * 32, gk0 + ks, lane);
+        fb[ks] = read_frag<true, TU::LD>(uk, 0, gk0 + ks, lane);
       }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) fd[ks] = read_frag<false, TDN::LD>(dn, uc * 32, ks, lane);   // columns, k = tokens
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 csum;
 #pragma unroll
       for (int r = 0; r < 16; ++r) csum[r] = 0.f;
+      // three independent accumulation chains, interleaved
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 fd = read_frag<false, TDN::LD>(dn, uc * 32, ks, lane);      // columns, k = tokens
-        const bf16x8 fz = read_frag<false, L::Z_LD>(Zs, 0, ks, lane);            // rows r, k = tokens
-        accu[cp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd, fz, accu[cp], 0, 0, 0);
-        if (do_colsum) csum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd, ones, csum, 0, 0, 0);
+        accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fa[ks], accg, 0, 0, 0);
+        accu[cp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[ks], fz[ks], accu[cp], 0, 0, 0);
+        csum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[ks], ones, csum, 0, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
       // every row of csum holds the same column sums; lanes 0 and 32 keep them
-      if (do_colsum && (lane & 31) == 0) {
+      if ((lane & 31) == 0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
           *reinterpret_cast<float4*>(dbs + cp * CW + uc * 32 + q * 8 + (lane >> 5) * 4) =
@@ -262,20 +295,21 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     // ---- flush the pass: dU blocks through the wave's strip as whole lines, then the sums ----
     static_for<0, PASS>([&](auto cpc) {
       constexpr int cp = cpc.value;
+      if (c0 + cp >= n_chunks) return;
       const int col0 = (c0 + cp) * CW + uc * 32;
       const int row = lane & 31;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int piece = q * 2 + (lane >> 5);
-        *reinterpret_cast<float4*>(ustrip + row * 128 + ((piece ^ (row & 7)) * 16)) =
+        *reinterpret_cast<float4*>(strip + row * 128 + ((piece ^ (row & 7)) * 16)) =
             make_float4(accu[cp][q * 4 + 0], accu[cp][q * 4 + 1], accu[cp][q * 4 + 2], accu[cp][q * 4 + 3]);
       }
 #pragma unroll
       for (int r0 = 0; r0 < 32; r0 += 8) {
         const int r = r0 + (lane >> 3), piece = lane & 7;
-        const float4 v = *reinterpret_cast<const float4*>(ustrip + r * 128 + ((piece ^ (r & 7)) * 16));
+        const float4 v = *reinterpret_cast<const float4*>(strip + r * 128 + ((piece ^ (r & 7)) * 16));
         const int gn = col0 + piece * 4;
-        if (c0 + cp < n_chunks && r < p.R && gn < p.N)
+        if (r < p.R && gn < p.N)
           *reinterpret_cast<float4*>(p.du_slabs + ((int64_t)tile_m * p.R + r) * p.N + gn) = v;
       }
     });
@@ -309,7 +343,6 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   // G, rounded to bf16, row-major, once the two partial sums of each block are added
   float* const Gx = reinterpret_cast<float*>(work);                    // [2 blocks][64 lanes][16]
   bf16* const Gs = reinterpret_cast<bf16*>(work + 16384);
-  unsigned char* const strip = work + 16384 + 64 * L::G_LD * 2 + wave * 8192;   // [64 rows][128 bytes]
   __syncthreads();   // the chunk buffers are idle
   if (wave >= 2) {
 #pragma unroll
@@ -342,6 +375,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
 #pragma unroll
   for (int t = 0; t < L::DX_GROUPS; ++t) {
     const int g = wave + 4 * t;
+    if (g >= n_groups) break;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -367,8 +401,8 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
       const int row = r0 + (lane >> 3), piece = lane & 7;
       const uint4 v = *reinterpret_cast<const uint4*>(strip + row * 128 + ((piece ^ (row & 7)) * 16));
       const int gn = g * 64 + piece * 8;
-      // rows past M fall outside the window; groups and columns past the end are pointed there
-      window_store16(dxw, (g < n_groups && gn < p.K1) ? (unsigned)(row * p.K1 + gn) * 2u : OOB_OFFSET, v);
+      // rows past M fall outside the window; columns past the end are pointed there
+      window_store16(dxw, gn < p.K1 ? (unsigned)(row * p.K1 + gn) * 2u : OOB_OFFSET, v);
     }
   }
 }

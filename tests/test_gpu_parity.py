@@ -290,7 +290,8 @@ NARROW_CASES = [
     # counts on both sides of a pass of eight (out = 1024 | 1040 | 2320), R below the kernel's
     # width, the longest input it takes
     (W.scaled(W.BERT_BASE_PROJ[0], tokens=16384), False),
-    (W.Workload("narrow_many_tiles", 20000, 96, 160, 1, 32, "bf16", seed=36), False),
+    (W.Workload("narrow_many_tiles", 15000, 96, 160, 1, 32, "bf16", seed=36), False),
+    (W.Workload("narrow_two_rounds", 20000, 96, 160, 1, 32, "bf16", seed=36), True),
     (W.scaled(W.BERT_BASE_PROJ[0], tokens=1237), True),
     (W.Workload("narrow_r16", 3333, 144, 336, 1, 16, "bf16", seed=37), True),
     (W.Workload("narrow_one_chunk", 130, 64, 48, 1, 16, "bf16", seed=32), True),
