@@ -47,7 +47,9 @@ def oracle_all(t: W.Tensors):
     )
 
 
-def check_all(sk, w: W.Workload, plan: int, with_bias=True):
+def check_all(sk, w: W.Workload, plan: int, with_bias=True, single_call=False):
+    """The three calls against the oracle; with single_call also sk_linear_bwd (the backward
+    pass of the benchmark's timed step) on buffers of its own."""
     print(f"case {w.name} T={w.tokens} in={w.d_in} out={w.d_out} l={w.l} k={w.k} "
           f"{w.dtype} plan={plan} bias={with_bias}", flush=True)
     sk.sk_set_plan(plan)
@@ -65,6 +67,14 @@ def check_all(sk, w: W.Workload, plan: int, with_bias=True):
         assert e <= TOL[w.dtype], (n, e)
     for n, e in errs2.items():
         assert e <= TOL[w.dtype], (n, "max|g-o|/max|o|", e)
+    if single_call:
+        one = DeviceLayer(t, sk)
+        sk.check(one.bwd())
+        torch.cuda.synchronize()
+        for n, g in (("dX", one.dX), ("dU", one.dU), ("db", one.db)):
+            e, e2 = rel_err(to_f64(g), want[n]), abs_err_scaled(to_f64(g), want[n])
+            print(f"   sk_linear_bwd {n}: {e:.2e}, {e2:.2e}", flush=True)
+            assert e <= TOL[w.dtype] and e2 <= TOL[w.dtype], ("sk_linear_bwd", n, e, e2)
     return errs
 
 
@@ -114,7 +124,7 @@ def test_no_bias_and_no_dbias(sk, plan):
 @pytest.mark.parametrize("w", (W.BERT_BASE_FFN_UP,) + W.BERT_BASE_PROJ +
                          (W.BERT_LARGE_FFN_UP, W.BERT_LARGE_FFN_DOWN), ids=lambda w: w.name)
 def test_parity_full_size(sk, w):
-    check_all(sk, w, 0)
+    check_all(sk, w, 0, single_call=True)
 
 
 def _kernels_of(sk, dev, calls=("fwd", "bwd_input", "bwd_weight")):
@@ -164,6 +174,14 @@ def test_parity_llm_mlp_full_size(sk):
     dev = DeviceLayer(t, sk)
     dev.run_all()
     _check_whole_tensors(sk, w, t, dev)
+    # the backward pass of the benchmark's timed step: at this size sk_linear_bwd runs the same
+    # kernels as the two separate calls, so its results are theirs bit for bit
+    one = DeviceLayer(t, sk)
+    sk.check(one.bwd())
+    torch.cuda.synchronize()
+    assert torch.equal(one.dX.view(torch.int16), dev.dX.view(torch.int16))
+    assert torch.equal(one.dU.view(torch.int32), dev.dU.view(torch.int32))
+    assert torch.equal(one.db.view(torch.int32), dev.db.view(torch.int32))
 
 
 def test_parity_big_tile_paths_mid_size(sk):
