@@ -137,9 +137,9 @@ sk_status sk_linear_bwd_weight_noalloc(const void* x, const void* S_cat, const v
  * dY . U_cat^T runs beside the recomputation of x . S_cat, and the sum of the factor
  * gradient's token splits rides on the kernel that expands dX -- three launches instead
  * of five, which is most of the cost at BERT-base sizes.  For very narrow sketches
- * (bf16, R <= 32, in <= 848) over 8129 to 16384 tokens (while out is small enough for
+ * (bf16, R <= 32, in <= 848) over up to 16384 tokens (while out is small enough for
  * the per-tile partial sums) one kernel reads x and dY once, recomputes x . S_cat,
- * and produces dX and a partial dU_cat and dbias per 64-token tile, which a second kernel
+ * and produces dX and a partial dU_cat and dbias per token tile, which a second kernel
  * sums in tile order: two launches, dY read once; dU_cat and dbias then differ from the
  * separate call's in the order of their fp32 partial sums (they remain bit-reproducible
  * from run to run).  Other shapes run the two gradients one after the other.

@@ -31,7 +31,8 @@ typedef enum {
   SK_TUNE_STILE = 5,    /* tile of the split first contraction of the split+expand plan */
   SK_TUNE_SSPLITS = 6,  /* number of splits of that contraction */
   SK_TUNE_NARROW_BWD = 7, /* sk_linear_bwd's one-pass schedule for narrow sketches: 0 = never, 1 = wherever
-                           the kernel can serve the shape */
+                           the kernel can serve the shape, 32 or 64 = the same with that many tokens per
+                           work-group */
   SK_TUNE_COUNT = 8
 } sk_tune_knob;
 

@@ -479,19 +479,19 @@ size_t first_stage_bytes(const Shape& s, int64_t nc) {
 }
 
 // Both gradients of a narrow sketch in one pass over x and dY (sk_bwd_narrow.hip): a
-// work-group per 64-token tile produces its rows of dX outright and leaves one fp32 slab of
-// dU_cat (and of dbias) behind, which a second kernel sums; G never leaves the chip and
-// three launches become two.  A work-group is four waves on a CU of its own, so nothing
-// hides its latencies but its own prefetching, and it takes about 16 us for its tile
-// whatever the token count; the launch pays when its one round of work-groups covers at
-// least half of the chip.  Measured on MI355X (in = out = 768, R = 32, backward call, one
-// pass against the three-launch schedule): 4096 tokens 24.5 / 22.9 us, 8192 27.2 / 30.7,
-// 12288 30.4 / 35.4, 16384 33.9 / 39.1, 20480 (a second, quarter-full round) 52.9 / 44.5;
-// R = 64 (a variant of the kernel since removed) lost at every size.  So: R <= 32, between
-// half a round and one round of token tiles, slabs of at most 32 MiB.
+// work-group per tile of 32 or 64 tokens produces its rows of dX outright and leaves one
+// fp32 slab of dU_cat (and of dbias) behind, which a second kernel sums; G never leaves the
+// chip and three launches become two.  A work-group is four waves on a CU of its own, so
+// nothing hides its latencies but its own prefetching, and it takes 13-18 us for its tile
+// whatever the token count; a second round of work-groups doubles that.  Measured on MI355X
+// (in = out = 768, R = 32, backward call; 32-token tiles / 64-token tiles / the three-launch
+// schedule, us): 512 tokens 16.2 / - / 20.7, 2048 18.4 / 22.1 / 22.6, 4096 21.1 / 24.4 /
+// 23.2, 8192 25.9 / 27.5 / 30.5, 12288 41.4 / 30.7 / 35.4, 16384 46.3 / 34.8 / 38.8, 20480
+// - / 52.9 / 44.5; R = 64 (a variant of the kernel since removed) lost at every size.
+// So: R <= 32, one round of work-groups, slabs of at most 32 MiB.
 struct NarrowPlan {
   bool ok;
-  int tiles_m;
+  int tm, tiles_m;   // tokens per work-group (32 or 64), work-groups
   size_t du_bytes, db_bytes;
   size_t total() const { return du_bytes + db_bytes; }
 };
@@ -501,13 +501,22 @@ NarrowPlan plan_narrow(const Shape& s) {
   const int forced = tune(SK_TUNE_NARROW_BWD);
   if (s.dtype != SK_BF16 || g_plan.load(std::memory_order_relaxed) != PLAN_AUTO || forced == 0) return n;
   if (s.in > narrow_bwd_max_in(s.R)) return n;   // (0 for a sketch the kernel does not serve)
-  const int64_t tiles_m = (s.T + 63) / 64;
-  const size_t du = (size_t)tiles_m * s.R * s.out * 4;
-  if (forced < 0 && (du > ((size_t)32 << 20) || tiles_m < NUM_CUS / 2 || tiles_m > NUM_CUS)) return n;
-  n.ok = true;
-  n.tiles_m = (int)tiles_m;
-  n.du_bytes = align_up(du);
-  n.db_bytes = align_up((size_t)tiles_m * s.out * 4);
+  // 32-token tiles while they make one round of work-groups with slabs under the cap, 64-token
+  // tiles beyond; a few work-groups only where each has little to walk
+  for (int tm = 32; tm <= 64; tm *= 2) {
+    if ((forced == 32 || forced == 64) && tm != forced) continue;
+    const int64_t tiles_m = (s.T + tm - 1) / tm;
+    const size_t du = (size_t)tiles_m * s.R * s.out * 4;
+    const bool fits = du <= ((size_t)32 << 20) && tiles_m <= NUM_CUS && (tiles_m >= NUM_CUS / 4 || s.out <= 1024);
+    if (forced < 0 && !fits) continue;
+    if (forced == 1 && !fits && tm == 32) continue;   // forced without a tile height: 64 unless 32 fits
+    n.ok = true;
+    n.tm = tm;
+    n.tiles_m = (int)tiles_m;
+    n.du_bytes = align_up(du);
+    n.db_bytes = align_up((size_t)tiles_m * s.out * 4);
+    return n;
+  }
   return n;
 }
 
@@ -948,7 +957,7 @@ sk_status sk_linear_bwd(const void* x, const void* dY, const void* S_cat, const 
     b.x = x; b.S = S_cat; b.dY = dY; b.U = U_cat; b.dX = dX;
     b.du_slabs = reinterpret_cast<float*>(ws_in);
     b.db_slabs = dbias ? reinterpret_cast<float*>(ws_in + n.du_bytes) : nullptr;
-    b.M = (int)tokens; b.K1 = (int)in; b.R = s.R; b.N = (int)out; b.scale = scale;
+    b.M = (int)tokens; b.K1 = (int)in; b.R = s.R; b.N = (int)out; b.scale = scale; b.tm = n.tm;
     hipError_t e = launch_bwd_narrow_bf16(b, hs);
     if (e != hipSuccess) return hip_fail(e, "sk_linear_bwd (one pass over x and dY)");
     ReduceArgs t{};

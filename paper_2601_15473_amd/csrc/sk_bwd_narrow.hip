@@ -4,8 +4,8 @@
 // columns, dU_cat = Z^T . dY over the tokens -- so a kernel that wants each dY tile only
 // once has to own whole rows of dY (for G, and through it dX) and leave one partial sum of
 // dU_cat per token tile behind.  For a narrow sketch over a layer of moderate width that
-// partial sum is small, and this kernel does it: a work-group owns 64 tokens and
-//   1. recomputes its Z tile = x_tile . S_cat (64 x R; never read from a saved copy):
+// partial sum is small, and this kernel does it: a work-group owns 32 or 64 tokens and
+//   1. recomputes its Z tile = x_tile . S_cat (tokens x R; never read from a saved copy):
 //      S_cat sits in LDS whole and the four waves split the contraction four ways.  A wave
 //      loads its quarter of the x tile as whole 128-byte row segments and turns them into
 //      MFMA fragments through an LDS strip of its own, so this stage needs no barrier
@@ -34,8 +34,11 @@
 
 namespace sk {
 
+// NI = 32-token blocks per work-group: a work-group owns TMK = 32 NI tokens (32 or 64).
+template <int NI>
 struct NarrowLds {
   static constexpr int RT = 32;             // sketch columns the kernel is built for (R <= RT)
+  static constexpr int TMK = 32 * NI;       // tokens per work-group
   static constexpr int CW = 128;            // columns of dY per chunk
   // Row stride of the two tiles that are read with the LDS transpose read (S_cat and Z, both
   // [k][R]): 24 dwords modulo 32, so the four k rows a 16-lane group reads (8 dwords each)
@@ -49,31 +52,38 @@ struct NarrowLds {
   static constexpr int DX_GROUPS = ((MAX_IN + 63) / 64 + 3) / 4;     // 64-column groups of dX per wave
   static constexpr int Z_LD = S_LD;
   static constexpr int G_LD = RT + 8;       // G tile, [tokens][R] row-major (read_frag_rowmajor's padding)
-  typedef OpTile<64, true, CW, 256> TDK;    // dY chunk, [tokens][columns], columns = k of G
-  typedef OpTile<CW, false, 64, 256> TDN;   // dY chunk, [tokens = k of dU][columns]
+  typedef OpTile<TMK, true, CW, 256> TDK;   // dY chunk, [tokens][columns], columns = k of G
+  typedef OpTile<CW, false, TMK, 256> TDN;  // dY chunk, [tokens = k of dU][columns]
   typedef OpTile<RT, true, CW, 256> TU;     // U_cat chunk, [R rows][columns = k of G]
   static constexpr int CHUNK_BYTES = (TDK::ELEMS + TDN::ELEMS + TU::ELEMS) * 2;
   static constexpr int PASS = 8;            // chunks between flushes: PASS x 16 accumulators
   static constexpr int NSET = 4;            // chunks in flight (register sets); divides PASS
+  // G = dY . U^T: each of the NI token blocks has KP partial sums over parts of a chunk's
+  // columns (one per wave), added when the chunks are done.
+  static constexpr int KP = 4 / NI;
+  static constexpr int GK = (CW / 16) / KP; // k steps of G per chunk and wave
   // LDS map: Z tile | column sums of a pass | an 8 KB strip per wave (x sub-tiles, then the dU
   // flush, then dX) | work.
   // work: S_cat (stages 0-1); then two chunk buffers, the partial Z tiles on top of the
-  // second one (dead before it is first filled); at the end G and the dX strips.
-  static constexpr int Z_BYTES = 64 * Z_LD * 2;
+  // second one (dead before it is first filled); at the end the partial sums of G and G.
+  static constexpr int Z_BYTES = TMK * Z_LD * 2;
   static constexpr int DB_BYTES = PASS * CW * 4;
   static constexpr int STRIP_BYTES = 4 * 8192;
   static constexpr int ZPART_OFF = CHUNK_BYTES;
-  static constexpr int ZPART_BYTES = 4 * 64 * RT * 4;
+  static constexpr int ZPART_BYTES = 4 * TMK * RT * 4;
   static constexpr int AFTER_S = ZPART_OFF + (ZPART_BYTES > CHUNK_BYTES ? ZPART_BYTES : CHUNK_BYTES);
   static constexpr int WORK_BYTES = S_CAP > AFTER_S ? S_CAP : AFTER_S;
   static constexpr int BYTES = Z_BYTES + DB_BYTES + STRIP_BYTES + WORK_BYTES;
+  static constexpr int GX_BYTES = 16384;
   static_assert(BYTES <= 160 * 1024, "over the LDS of a compute unit");
-  static_assert(16384 + 64 * G_LD * 2 <= WORK_BYTES, "stage 3: G partials, G tile");
+  static_assert((KP - 1) * NI * 64 * 16 * 4 <= GX_BYTES && GX_BYTES + TMK * G_LD * 2 <= WORK_BYTES,
+                "stage 3: partial sums of G, G tile");
   static_assert(PASS % NSET == 0 && NSET % 2 == 0, "register sets and LDS buffers rotate with the pass");
+  static_assert(TMK * 128 <= 8192 && TMK * 64 * 2 <= 8192, "the wave's strip holds a dX block and an x sub-tile");
 };
 
 // The largest `in` whose S_cat fits the kernel's LDS budget for this sketch width.
-int narrow_bwd_max_in(int R) { return R <= NarrowLds::RT ? NarrowLds::MAX_IN : 0; }
+int narrow_bwd_max_in(int R) { return R <= NarrowLds<2>::RT ? NarrowLds<2>::MAX_IN : 0; }
 
 // 16-byte store through a buffer window: dropped when the offset is past the end.
 __device__ __forceinline__ void window_store16(const GWindow& w, unsigned byte_off, const uint4& v) {
@@ -81,12 +91,13 @@ __device__ __forceinline__ void window_store16(const GWindow& w, unsigned byte_o
   __builtin_amdgcn_raw_buffer_store_b128(d, w.rsrc, (int)byte_off, 0, 0);
 }
 
+template <int NI>
 __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) {
-  typedef NarrowLds L;
-  typedef L::TDK TDK;
-  typedef L::TDN TDN;
-  typedef L::TU TU;
-  constexpr int RT = L::RT;
+  typedef NarrowLds<NI> L;
+  typedef typename L::TDK TDK;
+  typedef typename L::TDN TDN;
+  typedef typename L::TU TU;
+  constexpr int RT = L::RT, TMK = L::TMK;
   constexpr int NSET = L::NSET, PASS = L::PASS, CW = L::CW;
   __shared__ __attribute__((aligned(16))) unsigned char smem[L::BYTES];
   bf16* const Zs = reinterpret_cast<bf16*>(smem);
@@ -97,7 +108,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   unsigned char* const strip = smem + L::Z_BYTES + L::DB_BYTES + wave * 8192;   // this wave's own
   const int tile_m = blockIdx.x;
-  const int m0 = tile_m * 64;
+  const int m0 = tile_m * TMK;
 
   const bf16* __restrict__ X = static_cast<const bf16*>(p.x);
   const bf16* __restrict__ S = static_cast<const bf16*>(p.S);
@@ -122,13 +133,14 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   const int per_wave = (steps + 3) / 4;
   const int s_begin = wave * per_wave;
   const int s_end = (s_begin + per_wave < steps) ? s_begin + per_wave : steps;
-  uint4 xv[L::X_SUBS][8];
+  constexpr int XP = TMK * 8 / 64;   // 16-byte pieces of a sub-tile per lane
+  uint4 xv[L::X_SUBS][XP];
   {
     const GWindow xw = make_window(X, (int64_t)m0 * p.K1, (int64_t)p.M * p.K1, 2);
 #pragma unroll
     for (int t = 0; t < L::X_SUBS; ++t)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < XP; ++u) {
         const int q = u * 64 + lane;
         const int row = q >> 3, k = (s_begin + t * 4) * 16 + (q & 7) * 8;
         // (rows past M fall outside the window by themselves)
@@ -156,58 +168,58 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
 
   // ---------------- stage 1: Z tile, the contraction split over the four waves ----------------
   {
-    f32x16 accz[2];
+    f32x16 accz[NI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) accz[i][r] = 0.f;
-    bf16* const xt = reinterpret_cast<bf16*>(strip);   // [64 rows][64 k], pieces swizzled by row
+    bf16* const xt = reinterpret_cast<bf16*>(strip);   // [TMK rows][64 k], pieces swizzled by row
 #pragma unroll
     for (int t = 0; t < L::X_SUBS; ++t) {
       if (s_begin + t * 4 >= s_end) break;   // (the loops are sized for the longest input)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < XP; ++u) {
         const int q = u * 64 + lane;
         const int row = q >> 3;
         *reinterpret_cast<uint4*>(xt + row * 64 + kc_piece<64>(row, q & 7) * 8) = xv[t][u];
       }
-      bf16x8 fx[4][2], fb[4];
+      bf16x8 fx[4][NI], fb[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         // (past the wave's range the x fragments are zero; any valid k step serves for S_cat)
         const int kg = s_begin + t * 4 + ks < s_end ? s_begin + t * 4 + ks : 0;
         fb[ks] = read_frag<false, L::S_LD>(Ss, 0, kg, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fx[ks][i] = read_frag<true, 64>(xt, i * 32, ks, lane);
+        for (int i = 0; i < NI; ++i) fx[ks][i] = read_frag<true, 64>(xt, i * 32, ks, lane);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NI; ++i)
           accz[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fx[ks][i], accz[i], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();   // everybody is done with S_cat: part of its region now takes the partial tiles
     float* const Zpart = reinterpret_cast<float*>(work + L::ZPART_OFF);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int row = i * 32 + (lane & 31), col = q * 8 + (lane >> 5) * 4;
-        *reinterpret_cast<float4*>(Zpart + (wave * 64 + row) * RT + col) =
+        *reinterpret_cast<float4*>(Zpart + (wave * TMK + row) * RT + col) =
             make_float4(accz[i][q * 4 + 0], accz[i][q * 4 + 1], accz[i][q * 4 + 2], accz[i][q * 4 + 3]);
       }
     __syncthreads();
     // the four partial tiles summed in wave order, rounded once to bf16
 #pragma unroll
-    for (int u = 0; u < (64 * RT / 4) / 256; ++u) {
+    for (int u = 0; u < (TMK * RT / 4) / 256; ++u) {
       const int q = u * 256 + tid;
       const int row = q / (RT / 4), c = (q % (RT / 4)) * 4;
       float4 s = *reinterpret_cast<const float4*>(Zpart + row * RT + c);
 #pragma unroll
       for (int w = 1; w < 4; ++w) {
-        const float4 v = *reinterpret_cast<const float4*>(Zpart + (w * 64 + row) * RT + c);
+        const float4 v = *reinterpret_cast<const float4*>(Zpart + (w * TMK + row) * RT + c);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
       }
       uint2 o;
@@ -217,9 +229,10 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     }
   }
   __syncthreads();   // Z tile complete
-  bf16x8 fz[4];      // its fragments (rows r, k = tokens) serve every chunk
+  constexpr int UK = TMK / 16;   // k steps (tokens) of the dU product
+  bf16x8 fz[UK];                 // the Z tile's fragments (rows r, k = tokens) serve every chunk
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) fz[ks] = read_frag<false, L::Z_LD>(Zs, 0, ks, lane);
+  for (int ks = 0; ks < UK; ++ks) fz[ks] = read_frag<false, L::Z_LD>(Zs, 0, ks, lane);
 
   // ---------------- stage 2: the rows of dY, one 128-column chunk at a time ----------------
   auto store_chunk = [&](int buf, const uint4 (&d)[TDK::PIECES], const uint4 (&u)[TU::PIECES]) {
@@ -230,11 +243,11 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   };
 
   // A wave's share of a chunk.
-  //   G [64 tokens x R]: the 32-token block gi = wave % 2 over half of the chunk's columns
-  //   (so each block has two partial sums, added at the end);
+  //   G [TMK tokens x R]: the 32-token block gi over part kp of the chunk's columns (KP
+  //   partial sums per block, added at the end);
   //   dU [R x 128 columns]: the 32 columns uc = wave.
-  constexpr int GK = 4;                  // k steps of G per chunk and wave
-  const int gi = wave & 1, gk0 = (wave >> 1) * 4;
+  constexpr int GK = L::GK, KP = L::KP;
+  const int gi = wave % NI, kp = wave / NI, gk0 = kp * GK;
   const int uc = wave;
   f32x16 accg;
 #pragma unroll
@@ -263,24 +276,26 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
       const bf16* dk = reinterpret_cast<const bf16*>(work + buf * L::CHUNK_BYTES);
       const bf16* dn = dk + TDK::ELEMS;
       const bf16* uk = dn + TDN::ELEMS;
-      bf16x8 fa[GK], fb[GK], fd[4];
+      bf16x8 fa[GK], fb[GK], fd[UK];
 #pragma unroll
       for (int ks = 0; ks < GK; ++ks) {
         fa[ks] = read_frag<true, TDK::LD>(dk, gi * 32, gk0 + ks, lane);
         fb[ks] = read_frag<true, TU::LD>(uk, 0, gk0 + ks, lane);
       }
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) fd[ks] = read_frag<false, TDN::LD>(dn, uc * 32, ks, lane);   // columns, k = tokens
+      for (int ks = 0; ks < UK; ++ks) fd[ks] = read_frag<false, TDN::LD>(dn, uc * 32, ks, lane);   // columns, k = tokens
       __builtin_amdgcn_sched_barrier(0);
       f32x16 csum;
 #pragma unroll
       for (int r = 0; r < 16; ++r) csum[r] = 0.f;
       // three independent accumulation chains, interleaved
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fa[ks], accg, 0, 0, 0);
-        accu[cp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[ks], fz[ks], accu[cp], 0, 0, 0);
-        csum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[ks], ones, csum, 0, 0, 0);
+      for (int ks = 0; ks < (GK > UK ? GK : UK); ++ks) {
+        if (ks < GK) accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks], fa[ks], accg, 0, 0, 0);
+        if (ks < UK) {
+          accu[cp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[ks], fz[ks], accu[cp], 0, 0, 0);
+          csum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[ks], ones, csum, 0, 0, 0);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
       // every row of csum holds the same column sums; lanes 0 and 32 keep them
@@ -340,24 +355,27 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
         const int n = g * 64 + jb * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
         fs[t][jb][ks] = window_load16(sw, (g < n_groups && n < p.K1 && k < p.R) ? (unsigned)(n * p.R + k) * 2u : OOB_OFFSET);
       }
-  // G, rounded to bf16, row-major, once the two partial sums of each block are added
-  float* const Gx = reinterpret_cast<float*>(work);                    // [2 blocks][64 lanes][16]
-  bf16* const Gs = reinterpret_cast<bf16*>(work + 16384);
+  // G, rounded to bf16, row-major, once the partial sums of each block are added (in order)
+  float* const Gx = reinterpret_cast<float*>(work);                    // [KP - 1][NI blocks][64 lanes][16]
+  bf16* const Gs = reinterpret_cast<bf16*>(work + L::GX_BYTES);
   __syncthreads();   // the chunk buffers are idle
-  if (wave >= 2) {
+  if (kp > 0) {
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      *reinterpret_cast<float4*>(Gx + ((gi * 64 + lane) * 16 + q * 4)) =
+      *reinterpret_cast<float4*>(Gx + ((((kp - 1) * NI + gi) * 64 + lane) * 16 + q * 4)) =
           make_float4(accg[q * 4 + 0], accg[q * 4 + 1], accg[q * 4 + 2], accg[q * 4 + 3]);
   }
   __syncthreads();
-  if (wave < 2) {
+  if (kp == 0) {
     const int row = gi * 32 + (lane & 31);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float4 a = make_float4(accg[q * 4 + 0], accg[q * 4 + 1], accg[q * 4 + 2], accg[q * 4 + 3]);
-      const float4 b = *reinterpret_cast<const float4*>(Gx + ((gi * 64 + lane) * 16 + q * 4));
-      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+#pragma unroll
+      for (int k2 = 1; k2 < KP; ++k2) {
+        const float4 b = *reinterpret_cast<const float4*>(Gx + ((((k2 - 1) * NI + gi) * 64 + lane) * 16 + q * 4));
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+      }
       const int col = q * 8 + (lane >> 5) * 4;
       uint2 o;
       o.x = pack_bf16x2(a.x, a.y);
@@ -366,9 +384,9 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     }
   }
   __syncthreads();   // G complete
-  bf16x8 fg[2][KS];
+  bf16x8 fg[NI][KS];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NI; ++i)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fg[i][ks] = read_frag_rowmajor<L::G_LD>(Gs, i * 32, ks, lane);
   const GWindow dxw = make_window(p.dX, (int64_t)m0 * p.K1, (int64_t)p.M * p.K1, 2);
@@ -377,7 +395,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     const int g = wave + 4 * t;
     if (g >= n_groups) break;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
         f32x16 acc;
@@ -397,7 +415,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
         }
       }
 #pragma unroll
-    for (int r0 = 0; r0 < 64; r0 += 8) {
+    for (int r0 = 0; r0 < TMK; r0 += 8) {
       const int row = r0 + (lane >> 3), piece = lane & 7;
       const uint4 v = *reinterpret_cast<const uint4*>(strip + row * 128 + ((piece ^ (row & 7)) * 16));
       const int gn = g * 64 + piece * 8;
@@ -457,8 +475,9 @@ hipError_t launch_reduce_tiles(const ReduceArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_bwd_narrow_bf16(NarrowBwdArgs a, hipStream_t s) {
-  if (a.R < 16 || a.R > NarrowLds::RT || a.K1 > NarrowLds::MAX_IN || a.M < 1) return hipErrorInvalidValue;
-  a.tiles_m = (a.M + 63) / 64;
+  typedef NarrowLds<2> L;
+  if (a.R < 16 || a.R > L::RT || a.K1 > L::MAX_IN || a.M < 1 || (a.tm != 32 && a.tm != 64)) return hipErrorInvalidValue;
+  a.tiles_m = (a.M + a.tm - 1) / a.tm;
   if (tracing()) {
     note_matrix(a.x, a.M, a.K1, a.K1, 2, false);
     note_matrix(a.S, a.K1, a.R, a.R, 2, false);
@@ -472,7 +491,9 @@ hipError_t launch_bwd_narrow_bf16(NarrowBwdArgs a, hipStream_t s) {
   w.flops = 2.0 * a.M * a.R * (2.0 * a.K1 + 2.0 * a.N);
   w.bytes = 2.0 * ((double)a.M * (2.0 * a.K1 + a.N) + (double)a.R * (a.K1 + a.N)) +
             4.0 * ((double)a.tiles_m * a.R * a.N + (double)a.tiles_m * a.N);
-  return launch_kernel("bwd_narrow_kernel", w, bwd_narrow_kernel, dim3((unsigned)a.tiles_m), dim3(256), s, a);
+  if (a.tm == 32)
+    return launch_kernel("bwd_narrow_kernel<1>", w, bwd_narrow_kernel<1>, dim3((unsigned)a.tiles_m), dim3(256), s, a);
+  return launch_kernel("bwd_narrow_kernel<2>", w, bwd_narrow_kernel<2>, dim3((unsigned)a.tiles_m), dim3(256), s, a);
 }
 
 }  // namespace sk

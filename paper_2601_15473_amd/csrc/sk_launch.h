@@ -212,8 +212,8 @@ constexpr int CHAIN_FUSED_MAX_R = 256;
 int chain_bn(int R);   // width of the N tiles the chain kernels walk
 hipError_t launch_chain_bf16(bool b_kc, bool fused, ChainArgs a, hipStream_t s);
 
-// Backward pass of a narrow sketch (bf16, R <= 64) in one pass over x and dY: per 64-token
-// tile the kernel recomputes Z = x . S_cat, forms G = dY . U_cat^T and from it the tile of
+// Backward pass of a narrow sketch (bf16, R <= 32) in one pass over x and dY: per token
+// tile (32 or 64 tokens) the kernel recomputes Z = x . S_cat, forms G = dY . U_cat^T and from it the tile of
 // dX, and leaves the tile's term of dU_cat (and of dbias) as an fp32 slab; a second kernel
 // (launch_reduce_tiles) sums the slabs in tile order.
 struct NarrowBwdArgs {
@@ -225,6 +225,7 @@ struct NarrowBwdArgs {
   float* du_slabs;   // [tiles_m][R][N]:  Z_tile^T . dY_tile
   float* db_slabs;   // [tiles_m][N]:     column sums of dY_tile, or null
   int M, K1, R, N;
+  int tm;            // tokens per work-group: 32 or 64
   int tiles_m;       // filled in by the launcher
   float scale;       // of dX
 };

@@ -303,25 +303,31 @@ def test_single_call_backward(sk, w):
 
 
 NARROW_CASES = [
-    # (workload, forced): the one-pass schedule where the planner takes it by itself (many
-    # token tiles) and forced onto small cases: ragged token tiles, a single chunk, chunk
-    # counts on both sides of a pass of eight (out = 1024 | 1040 | 2320), R below the kernel's
-    # width, the longest input it takes
-    (W.scaled(W.BERT_BASE_PROJ[0], tokens=16384), False),
-    (W.Workload("narrow_many_tiles", 15000, 96, 160, 1, 32, "bf16", seed=36), False),
-    (W.Workload("narrow_two_rounds", 20000, 96, 160, 1, 32, "bf16", seed=36), True),
-    (W.scaled(W.BERT_BASE_PROJ[0], tokens=1237), True),
-    (W.Workload("narrow_r16", 3333, 144, 336, 1, 16, "bf16", seed=37), True),
-    (W.Workload("narrow_one_chunk", 130, 64, 48, 1, 16, "bf16", seed=32), True),
-    (W.Workload("narrow_longest_in", 200, 848, 208, 2, 16, "bf16", seed=33), True),
-    (W.Workload("narrow_full_pass", 77, 400, 1024, 1, 32, "bf16", seed=34), True),
-    (W.Workload("narrow_pass_and_a_bit", 150, 112, 1040, 1, 32, "bf16", seed=38), True),
-    (W.Workload("narrow_three_passes", 100, 64, 2320, 2, 16, "bf16", seed=39), True),
-    (W.Workload("narrow_one_token", 1, 16, 16, 1, 16, "bf16", seed=35), True),
+    # (workload, forced tokens per work-group or None): the one-pass schedule where the planner
+    # takes it by itself (one round of token tiles: 32-token tiles up to 8192 tokens, 64-token
+    # tiles up to 16384) and forced onto small cases, both tile heights: ragged token tiles, a
+    # single chunk, chunk counts on both sides of a pass of eight (out = 1024 | 1040 | 2320), R
+    # below the kernel's width, the longest input it takes, a second round of work-groups
+    (W.BERT_BASE_PROJ[0], None),
+    (W.scaled(W.BERT_BASE_PROJ[0], tokens=16384), None),
+    (W.Workload("narrow_many_tiles", 15000, 96, 160, 1, 32, "bf16", seed=36), None),
+    (W.Workload("narrow_two_rounds", 20000, 96, 160, 1, 32, "bf16", seed=36), 64),
+    (W.scaled(W.BERT_BASE_PROJ[0], tokens=1237), 32),
+    (W.scaled(W.BERT_BASE_PROJ[0], tokens=1237), 64),
+    (W.Workload("narrow_r16", 3333, 144, 336, 1, 16, "bf16", seed=37), 32),
+    (W.Workload("narrow_one_chunk", 130, 64, 48, 1, 16, "bf16", seed=32), 64),
+    (W.Workload("narrow_one_chunk", 130, 64, 48, 1, 16, "bf16", seed=32), 32),
+    (W.Workload("narrow_longest_in", 200, 848, 208, 2, 16, "bf16", seed=33), 32),
+    (W.Workload("narrow_longest_in", 200, 848, 208, 2, 16, "bf16", seed=33), 64),
+    (W.Workload("narrow_full_pass", 77, 400, 1024, 1, 32, "bf16", seed=34), 64),
+    (W.Workload("narrow_pass_and_a_bit", 150, 112, 1040, 1, 32, "bf16", seed=38), 32),
+    (W.Workload("narrow_three_passes", 100, 64, 2320, 2, 16, "bf16", seed=39), 64),
+    (W.Workload("narrow_three_passes", 100, 64, 2320, 2, 16, "bf16", seed=39), 32),
+    (W.Workload("narrow_one_token", 1, 16, 16, 1, 16, "bf16", seed=35), 32),
 ]
 
 
-@pytest.mark.parametrize("w,forced", NARROW_CASES, ids=lambda v: v.name if hasattr(v, "name") else ("forced" if v else "auto"))
+@pytest.mark.parametrize("w,forced", NARROW_CASES, ids=lambda v: f"{v.name}_T{v.tokens}" if hasattr(v, "name") else (f"tm{v}" if v else "auto"))
 def test_one_pass_backward_for_narrow_sketches(sk, tuning, w, forced):
     """sk_linear_bwd's one-pass schedule (a kernel that reads x and dY once, writes dX and
     leaves a slab of dU and db per token tile, then the sum of the slabs): the kernel runs --
@@ -330,10 +336,12 @@ def test_one_pass_backward_for_narrow_sketches(sk, tuning, w, forced):
     print(f"case narrow {w.name} T={w.tokens} in={w.d_in} out={w.d_out} l={w.l} k={w.k} forced={forced}", flush=True)
     sk.sk_set_plan(0)
     if forced:
-        tuning(sk.SK_TUNE_NARROW_BWD, 1)
+        tuning(sk.SK_TUNE_NARROW_BWD, forced)
     t = W.generate(w)
     names = _kernels_of(sk, DeviceLayer(t, sk), ("bwd",))
     assert len(names) == 2 and "bwd_narrow_kernel" in names[0] and "reduce_tiles" in names[1], names
+    if forced:
+        assert names[0] == f"bwd_narrow_kernel<{forced // 32}>", names
     dev = DeviceLayer(t, sk)
     sk.check(dev.bwd())
     torch.cuda.synchronize()

@@ -126,7 +126,7 @@ def _forced(r):
     if r.random() < 0.3:
         out.append((sk.SK_TUNE_BM, int(r.choice([64, 128]))))
     if r.random() < 0.3:
-        out.append((sk.SK_TUNE_NARROW_BWD, int(r.integers(0, 2))))
+        out.append((sk.SK_TUNE_NARROW_BWD, int(r.choice([0, 1, 32, 64]))))
     return tuple(out)
 
 
@@ -160,12 +160,12 @@ def test_one_pass_backward_stays_inside_the_buffers():
     sum of the token tiles' slabs), chosen by the planner on the first shape and forced on
     the others: ragged tokens, one chunk, several flush passes, the longest input."""
     r = np.random.default_rng(11)
-    shapes = [(16384, 768, 768, 2, 16, sk.SK_BF16), (8129, 96, 160, 1, 32, sk.SK_BF16),
+    shapes = [(16384, 768, 768, 2, 16, sk.SK_BF16), (4096, 768, 768, 2, 16, sk.SK_BF16), (8193, 96, 160, 1, 32, sk.SK_BF16),
               (1237, 768, 768, 2, 16, sk.SK_BF16), (130, 64, 48, 1, 16, sk.SK_BF16),
               (200, 848, 208, 2, 16, sk.SK_BF16), (100, 64, 2320, 2, 16, sk.SK_BF16),
               (1, 16, 16, 1, 16, sk.SK_BF16), (70000, 848, 4096, 1, 32, sk.SK_BF16)]
     for i, shape in enumerate(shapes):
-        forced = () if i < 2 else ((sk.SK_TUNE_NARROW_BWD, 1),)
+        forced = () if i < 3 else ((sk.SK_TUNE_NARROW_BWD, (1, 32, 64)[i % 3]),)
         for knob, value in forced:
             sk.sk_set_tuning(knob, value)
         try:
