@@ -56,3 +56,45 @@ def test_calls_replay_from_a_graph(sk, w):
             got, want = getattr(dev, n), ref[n]
             assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
                                want.view(torch.int16 if want.dtype == torch.bfloat16 else torch.int32)), (rep, n)
+
+
+STEP_CASES = [
+    W.scaled(W.BERT_BASE_FFN_UP, tokens=1000),      # backward pass with shared launches, sums carried by the expansion
+    W.scaled(W.BERT_LARGE_FFN_UP, tokens=5000),     # two dual launches + the split sum
+    W.scaled(W.BERT_BASE_PROJ[0], tokens=700),      # one-pass backward (32-token tiles) + the sum of the tiles' slabs
+    W.scaled(W.BERT_BASE_PROJ[0], tokens=9000),     # ... with 64-token tiles
+]
+
+
+@pytest.mark.parametrize("w", STEP_CASES, ids=lambda w: f"{w.name}_T{w.tokens}")
+def test_timed_step_replays_from_a_graph(sk, w):
+    """The benchmark's step (sk_linear_fwd + sk_linear_bwd) recorded once and replayed."""
+    sk.sk_set_plan(0)
+    t = W.generate(w)
+    eager = DeviceLayer(t, sk)
+    sk.check(eager.fwd())
+    sk.check(eager.bwd())
+    torch.cuda.synchronize()
+    ref = {n: getattr(eager, n).clone() for n in ("y", "dX", "dU", "db")}
+
+    dev = DeviceLayer(t, sk, poison=False)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        for st in (dev.fwd(stream), dev.bwd(stream)):
+            sk.check(st)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=stream):
+        cap = torch.cuda.current_stream()
+        for st in (dev.fwd(cap), dev.bwd(cap)):
+            sk.check(st)
+    for rep in range(3):
+        for n in ("y", "dX", "dU", "db"):
+            getattr(dev, n).fill_(float("nan"))     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in ("y", "dX", "dU", "db"):
+            got, want = getattr(dev, n), ref[n]
+            assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
+                               want.view(torch.int16 if want.dtype == torch.bfloat16 else torch.int32)), (rep, n)
