@@ -257,6 +257,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   for (int j = 0; j < 8; ++j) ones[j] = (bf16)1.0f;
   const bool do_colsum = p.db_slabs != nullptr;
   f32x16 accu[PASS];
+  const GWindow duw = make_window(p.du_slabs, (int64_t)tile_m * p.R * p.N, ((int64_t)tile_m + 1) * p.R * p.N, 4);
 
   for (int c0 = 0; c0 < n_chunks; c0 += PASS) {
 #pragma unroll
@@ -308,6 +309,9 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     });
 
     // ---- flush the pass: dU blocks through the wave's strip as whole lines, then the sums ----
+    // (per block: all four reads first, then four branch-free stores -- rows past R and
+    // columns past N are pointed outside the slab's window.  Writing block cp + 1 into a second
+    // slot of the strip before block cp is read back measured no faster.)
     static_for<0, PASS>([&](auto cpc) {
       constexpr int cp = cpc.value;
       if (c0 + cp >= n_chunks) return;
@@ -319,13 +323,16 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
         *reinterpret_cast<float4*>(strip + row * 128 + ((piece ^ (row & 7)) * 16)) =
             make_float4(accu[cp][q * 4 + 0], accu[cp][q * 4 + 1], accu[cp][q * 4 + 2], accu[cp][q * 4 + 3]);
       }
+      uint4 v[4];
 #pragma unroll
-      for (int r0 = 0; r0 < 32; r0 += 8) {
-        const int r = r0 + (lane >> 3), piece = lane & 7;
-        const float4 v = *reinterpret_cast<const float4*>(strip + r * 128 + ((piece ^ (r & 7)) * 16));
-        const int gn = col0 + piece * 4;
-        if (r < p.R && gn < p.N)
-          *reinterpret_cast<float4*>(p.du_slabs + ((int64_t)tile_m * p.R + r) * p.N + gn) = v;
+      for (int u = 0; u < 4; ++u) {
+        const int r = u * 8 + (lane >> 3), piece = lane & 7;
+        v[u] = *reinterpret_cast<const uint4*>(strip + r * 128 + ((piece ^ (r & 7)) * 16));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int r = u * 8 + (lane >> 3), gn = col0 + (lane & 7) * 4;
+        window_store16(duw, (r < p.R && gn < p.N) ? (unsigned)(r * p.N + gn) * 4u : OOB_OFFSET, v[u]);
       }
     });
     if (do_colsum) {
@@ -414,13 +421,17 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
           *reinterpret_cast<uint2*>(strip + row * 128 + ((piece ^ (row & 7)) * 16) + (lane >> 5) * 8) = o;
         }
       }
+    uint4 v[TMK / 8];
 #pragma unroll
-    for (int r0 = 0; r0 < TMK; r0 += 8) {
-      const int row = r0 + (lane >> 3), piece = lane & 7;
-      const uint4 v = *reinterpret_cast<const uint4*>(strip + row * 128 + ((piece ^ (row & 7)) * 16));
-      const int gn = g * 64 + piece * 8;
+    for (int u = 0; u < TMK / 8; ++u) {
+      const int row = u * 8 + (lane >> 3), piece = lane & 7;
+      v[u] = *reinterpret_cast<const uint4*>(strip + row * 128 + ((piece ^ (row & 7)) * 16));
+    }
+#pragma unroll
+    for (int u = 0; u < TMK / 8; ++u) {
+      const int row = u * 8 + (lane >> 3), gn = g * 64 + (lane & 7) * 8;
       // rows past M fall outside the window; columns past the end are pointed there
-      window_store16(dxw, gn < p.K1 ? (unsigned)(row * p.K1 + gn) * 2u : OOB_OFFSET, v);
+      window_store16(dxw, gn < p.K1 ? (unsigned)(row * p.K1 + gn) * 2u : OOB_OFFSET, v[u]);
     }
   }
 }
