@@ -44,6 +44,12 @@ __device__ __forceinline__ uint4 window_load16(const GWindow& w, unsigned byte_o
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// 16-byte store through a window: dropped when the offset is at or past the window's end.
+__device__ __forceinline__ void window_store16(const GWindow& w, unsigned byte_off, const uint4& v) {
+  const u32x4 d = {v.x, v.y, v.z, v.w};
+  __builtin_amdgcn_raw_buffer_store_b128(d, w.rsrc, (int)byte_off, 0, 0);
+}
+
 // One operand tile of EXT rows (m or n extent) by KX (k extent, default BK) in LDS,
 // moved by a work-group of NTH threads.
 //   KC  = true : source is [EXT, K] with k contiguous; stored [EXT][KX] without padding,

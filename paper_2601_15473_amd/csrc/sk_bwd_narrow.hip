@@ -85,12 +85,6 @@ struct NarrowLds {
 // The largest `in` whose S_cat fits the kernel's LDS budget for this sketch width.
 int narrow_bwd_max_in(int R) { return R <= NarrowLds<2>::RT ? NarrowLds<2>::MAX_IN : 0; }
 
-// 16-byte store through a buffer window: dropped when the offset is past the end.
-__device__ __forceinline__ void window_store16(const GWindow& w, unsigned byte_off, const uint4& v) {
-  const u32x4 d = {v.x, v.y, v.z, v.w};
-  __builtin_amdgcn_raw_buffer_store_b128(d, w.rsrc, (int)byte_off, 0, 0);
-}
-
 template <int NI>
 __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) {
   typedef NarrowLds<NI> L;
