@@ -63,30 +63,33 @@ struct ReduceArgs {
 };
 
 // One segment of a split reduction, the part that falls to work-group `block` of `nblocks`
-// (256 threads each): 16-byte pieces are dealt round-robin, four per thread and pass so
-// that their loads overlap; every piece sums its slabs in index order.
-__device__ __forceinline__ void reduce_segment_part(const float* __restrict__ part, float* __restrict__ out,
+// (256 threads each): 16-byte pieces are dealt round-robin, U per thread and pass so that
+// their loads overlap; every piece sums its slabs in index order.  Every load is
+// unconditional -- a piece past the end re-reads the thread's first piece and is not
+// written -- so a pass issues all of its loads before it waits for any (under a per-piece
+// bounds branch the compiler waited for each load by itself).
+template <int U>
+__device__ __forceinline__ void reduce_segment_pass(const float* __restrict__ part, float* __restrict__ out,
                                                     int64_t n, int splits, float scale, int block,
                                                     int nblocks, int tid) {
-  constexpr int U = 4;
   const int64_t pieces = n / 4, stride = (int64_t)nblocks * 256;
   for (int64_t q0 = (int64_t)block * 256 + tid; q0 < pieces; q0 += stride * U) {
-    float4 s[U];
+    const float* src[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * stride;
-      s[u] = q < pieces ? *reinterpret_cast<const float4*>(part + q * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      src[u] = part + (q < pieces ? q : q0) * 4;
     }
+    float4 s[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) s[u] = *reinterpret_cast<const float4*>(src[u]);
 #pragma unroll 8
     for (int k = 1; k < splits; ++k) {
+      float4 v[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int64_t q = q0 + u * stride;
-        if (q < pieces) {
-          const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)k * n + q * 4);
-          s[u].x += v.x; s[u].y += v.y; s[u].z += v.z; s[u].w += v.w;
-        }
-      }
+      for (int u = 0; u < U; ++u) v[u] = *reinterpret_cast<const float4*>(src[u] + (int64_t)k * n);
+#pragma unroll
+      for (int u = 0; u < U; ++u) { s[u].x += v[u].x; s[u].y += v[u].y; s[u].z += v[u].z; s[u].w += v[u].w; }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -96,6 +99,14 @@ __device__ __forceinline__ void reduce_segment_part(const float* __restrict__ pa
             make_float4(s[u].x * scale, s[u].y * scale, s[u].z * scale, s[u].w * scale);
     }
   }
+}
+
+__device__ __forceinline__ void reduce_segment_part(const float* __restrict__ part, float* __restrict__ out,
+                                                    int64_t n, int splits, float scale, int block,
+                                                    int nblocks, int tid) {
+  // one piece per thread at most: no point in asking for four
+  if (n / 4 <= (int64_t)nblocks * 256) reduce_segment_pass<1>(part, out, n, splits, scale, block, nblocks, tid);
+  else reduce_segment_pass<4>(part, out, n, splits, scale, block, nblocks, tid);
 }
 
 // Both segments of a split reduction (see ReduceArgs), this work-group's part.
