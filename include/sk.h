@@ -132,17 +132,19 @@ sk_status sk_linear_bwd_weight_noalloc(const void* x, const void* S_cat, const v
  * Both gradients in one call: what sk_linear_bwd_input followed by sk_linear_bwd_weight
  * compute (same formulas, same outputs, same rounding points; the order of the fp32
  * partial sums inside dX may differ from the separate call's; dU_cat and dbias are
- * bit-identical to it except on the one-pass schedule below), scheduled together.  For
- * narrow sketches (bf16, R <= 128) kernels of the two gradients that do not depend on each other share launches --
- * dY . U_cat^T runs beside the recomputation of x . S_cat, and the sum of the factor
- * gradient's token splits rides on the kernel that expands dX -- three launches instead
- * of five, which is most of the cost at BERT-base sizes.  For very narrow sketches
- * (bf16, R <= 32, in <= 848) over up to 16384 tokens (while out is small enough for
- * the per-tile partial sums) one kernel reads x and dY once, recomputes x . S_cat,
- * and produces dX and a partial dU_cat and dbias per token tile, which a second kernel
- * sums in tile order: two launches, dY read once; dU_cat and dbias then differ from the
- * separate call's in the order of their fp32 partial sums (they remain bit-reproducible
- * from run to run).  Other shapes run the two gradients one after the other.
+ * bit-identical to it except on the one-pass schedule below), scheduled together.
+ *   - Narrow sketches (bf16, R <= 128): kernels of the two gradients that do not depend
+ *     on each other share launches -- dY . U_cat^T runs beside the recomputation of
+ *     x . S_cat, and the sum of the factor gradient's token splits rides on the kernel
+ *     that expands dX -- three launches instead of five, which is most of the cost at
+ *     BERT-base sizes.
+ *   - Very narrow sketches (bf16, R <= 32, in <= 848, out <= 896) over up to 16384
+ *     tokens: one kernel reads x and dY once, recomputes x . S_cat, and produces dX and
+ *     a partial dU_cat and dbias per token tile, which a second kernel sums in tile
+ *     order -- two launches, dY read once.  dU_cat and dbias then differ from the
+ *     separate call's in the order of their fp32 partial sums (they remain
+ *     bit-reproducible from run to run).
+ *   - Other shapes run the two gradients one after the other.
  *   x [tokens, in], dY [tokens, out], S_cat [in, R], U_cat [R, out],
  *   dX [tokens, in] (output), dU_cat [R, out] fp32 (output), dbias [out] fp32 (output) or NULL.
  * Workspace: sk_linear_workspace_bytes(SK_OP_BWD, ...) (at least the two gradients'

@@ -488,7 +488,11 @@ size_t first_stage_bytes(const Shape& s, int64_t nc) {
 // schedule, us): 512 tokens 16.2 / - / 20.7, 2048 18.4 / 22.1 / 22.6, 4096 21.1 / 24.4 /
 // 23.2, 8192 25.9 / 27.5 / 30.5, 12288 41.4 / 30.7 / 35.4, 16384 46.3 / 34.8 / 38.8, 20480
 // - / 52.9 / 44.5; R = 64 (a variant of the kernel since removed) lost at every size.
-// So: R <= 32, one round of work-groups, slabs of at most 32 MiB.
+// A sweep over in = 64..768 and out = 64..3072 at 256..16384 tokens (same call, one pass
+// over three launches): out <= 256 0.63-0.84, out = 768 0.80-1.04, out = 1024 0.83-1.14
+// (R = 16: 0.82-1.03), out = 2048 1.06-1.31, out = 3072 1.20-1.59 -- a work-group walks all
+// of `out`, and the walk is what it cannot hide.
+// So: R <= 32, out <= 896 (1024 for R = 16), one round of work-groups, slabs of at most 32 MiB.
 struct NarrowPlan {
   bool ok;
   int tm, tiles_m;   // tokens per work-group (32 or 64), work-groups
@@ -502,12 +506,12 @@ NarrowPlan plan_narrow(const Shape& s) {
   if (s.dtype != SK_BF16 || g_plan.load(std::memory_order_relaxed) != PLAN_AUTO || forced == 0) return n;
   if (s.in > narrow_bwd_max_in(s.R)) return n;   // (0 for a sketch the kernel does not serve)
   // 32-token tiles while they make one round of work-groups with slabs under the cap, 64-token
-  // tiles beyond; a few work-groups only where each has little to walk
+  // tiles beyond; only while a work-group's walk over `out` stays short
   for (int tm = 32; tm <= 64; tm *= 2) {
     if ((forced == 32 || forced == 64) && tm != forced) continue;
     const int64_t tiles_m = (s.T + tm - 1) / tm;
     const size_t du = (size_t)tiles_m * s.R * s.out * 4;
-    const bool fits = du <= ((size_t)32 << 20) && tiles_m <= NUM_CUS && (tiles_m >= NUM_CUS / 4 || s.out <= 1024);
+    const bool fits = du <= ((size_t)32 << 20) && tiles_m <= NUM_CUS && s.out <= (s.R <= 16 ? 1024 : 896);
     if (forced < 0 && !fits) continue;
     if (forced == 1 && !fits && tm == 32) continue;   // forced without a tile height: 64 unless 32 fits
     n.ok = true;
