@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
   const GWindow sw = make_window(S, 0, (int64_t)p.K1 * p.R, 2);
   const int n_chunks = (p.N + CW - 1) / CW;
 
-  // ---------------- every independent load, issued up front ----------------
+  // ---------------- every independent load, issued before the first barrier ----------------
   // S_cat, whole
   constexpr int PPR = RT / 8;
   const int s_pieces = p.K1 * PPR;
@@ -149,7 +149,6 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     TDK::load(d, DY, p.N, m0, p.M, c * CW, lim, p.N, tid);
     TU::load(u, U, p.N, 0, p.R, c * CW, lim, p.N, tid);
   };
-  static_for<0, NSET>([&](auto j) { load_chunk(rd[j.value], ru[j.value], j.value); });
 
   // ---------------- S_cat -> LDS ----------------
 #pragma unroll
@@ -158,6 +157,9 @@ __global__ __launch_bounds__(256) void bwd_narrow_kernel(const NarrowBwdArgs p) 
     const int k = q / PPR, c = (q % PPR) * 8;
     if (q < s_pieces) *reinterpret_cast<uint4*>(Ss + k * L::S_LD + c) = sv[u];
   }
+  // (the chunk loads go out only now: a wave issues in order, and S_cat cannot be stored
+  // before everything in front of that store has been issued -- about 16 cycles a load)
+  static_for<0, NSET>([&](auto j) { load_chunk(rd[j.value], ru[j.value], j.value); });
   __syncthreads();
 
   // ---------------- stage 1: Z tile, the contraction split over the four waves ----------------
