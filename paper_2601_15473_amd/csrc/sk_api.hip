@@ -513,7 +513,7 @@ NarrowPlan plan_narrow(const Shape& s) {
     const size_t du = (size_t)tiles_m * s.R * s.out * 4;
     const bool fits = du <= ((size_t)32 << 20) && tiles_m <= NUM_CUS && s.out <= (s.R <= 16 ? 1024 : 896);
     if (forced < 0 && !fits) continue;
-    if (forced == 1 && !fits && tm == 32) continue;   // forced without a tile height: 64 unless 32 fits
+    if (forced > 0 && forced != 32 && forced != 64 && !fits && tm == 32) continue;   // forced without a tile height: 64 unless 32 fits
     n.ok = true;
     n.tm = tm;
     n.tiles_m = (int)tiles_m;
