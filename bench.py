@@ -252,9 +252,11 @@ class Harness:
         return res, tensors, ops
 
 
-def measured_peaks(torch, stream):
+def measured_peaks(torch, stream, sk):
     """What this GPU gives a plain device-to-device copy (bytes read + written per second)
-    and a large square bf16 GEMM through hipBLASLt."""
+    and a large square bf16 GEMM through hipBLASLt -- and, like for like, what this library's
+    own GEMM kernel reaches on the same 8192^3 product (the two GEMMs of sk_linear_fwd on a
+    layer with tokens = in = out = R = 8192)."""
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
@@ -285,9 +287,32 @@ def measured_peaks(torch, stream):
             e1.record(stream)
             e1.synchronize()
             best_gemm = max(best_gemm, 2.0 * m ** 3 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    del a, b
+    own = 0.0
+    x = torch.randn(m, m, device="cuda", dtype=torch.bfloat16)
+    S = torch.randn(m, m, device="cuda", dtype=torch.bfloat16) * 0.01
+    U = torch.randn(m, m, device="cuda", dtype=torch.bfloat16) * 0.01
+    y = torch.empty(m, m, device="cuda", dtype=torch.bfloat16)
+    args = (m, m, m, 1, m, sk.SK_BF16)
+    ws_bytes = sk.sk_linear_workspace_bytes(sk.SK_OP_FWD, *args)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    with torch.cuda.stream(stream):
+        for _ in range(2):
+            sk.check(sk.sk_linear_fwd(x, S, U, None, y, *args, ws, ws_bytes, stream))
+        for _ in range(3):
+            e0.record(stream)
+            for _ in range(5):
+                sk.check(sk.sk_linear_fwd(x, S, U, None, y, *args, ws, ws_bytes, stream))
+            e1.record(stream)
+            e1.synchronize()
+            own = max(own, 2 * 2.0 * m ** 3 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    del x, S, U, y, ws
     torch.cuda.empty_cache()
     return {"hbm_copy_gbs": best_copy, "hbm_copy_what": "1 GiB device-to-device copy, bytes read + written per second",
-            "mfma_bf16_tflops": best_gemm, "mfma_what": "8192^3 bf16 GEMM, torch.matmul (hipBLASLt)"}
+            "mfma_bf16_tflops": best_gemm, "mfma_what": "8192^3 bf16 GEMM, torch.matmul (hipBLASLt)",
+            "own_gemm_bf16_tflops": own,
+            "own_gemm_what": "the same 8192^3 product by this library's GEMM kernel (sk_linear_fwd with "
+                             "tokens = in = out = R = 8192: two such GEMMs per call)"}
 
 
 def parity_stamp(torch, sk, W, dm):
@@ -459,7 +484,7 @@ def main():
 
     mp = None
     if not args.no_measured_peak:
-        mp = measured_peaks(torch, h.stream)
+        mp = measured_peaks(torch, h.stream, sk)
         mp["roofline_frac_of_measured"] = achieved / (mp["mfma_bf16_tflops"] if bound == "mfma" else mp["hbm_copy_gbs"])
         t_m = head["algorithmic_flops_per_step"] / (mp["mfma_bf16_tflops"] * 1e12)
         t_h = head["algorithmic_bytes_per_step"] / (mp["hbm_copy_gbs"] * 1e9)
